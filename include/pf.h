@@ -1,0 +1,205 @@
+/*
+ * pf.h -- C ABI of the ragged-cache attention library for MI355X (gfx950).
+ *
+ * The library implements the hot path of Pyramid Forcing's "Heterogeneous
+ * KVCache Computation Optimization" (paper Sec. 4.3) on top of the per-head
+ * cache policies of Sec. 4.2: every attention head of an autoregressive video
+ * DiT layer attends from the tokens of the chunk being generated to its OWN
+ * policy-selected set of history frames, so key/value lengths differ per head.
+ *
+ * Conventions
+ *  - Plain C.  Every function returns an int status (PF_OK or a negative
+ *    PF_ERR_* code), never throws, never allocates or frees device memory and
+ *    never synchronises with the device: all work is enqueued on the caller's
+ *    stream (a hipStream_t passed as void*; NULL = the default stream).
+ *  - Every buffer is owned by the caller.  "dev" = device memory, "host" = host
+ *    memory.  Device buffers must stay valid until the enqueued work has run.
+ *    Host structures are read during the call only; pf_cache_append and
+ *    pf_build_index update the host-side bookkeeping fields marked [lib].
+ *  - A "head" is one of the N = B x H independent sequences of Sec. 4.3
+ *    (batch-head order); the configurations used here have B = 1.
+ *  - A "frame" is one latent frame = tokens_per_frame tokens; history frames
+ *    carry global ids 0 .. T-1 and the chunk being generated starts at id T.
+ *  - K/V/Q/out elements are bfloat16 (dtype 0).  head_dim is 64 or 128.
+ *  - Calls that use the same pf_pool or pf_index must be ordered on one stream
+ *    (or otherwise serialised by the caller); concurrent use is a data race.
+ */
+#ifndef PF_H
+#define PF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PF_OK                 0
+#define PF_ERR_INVALID_ARG   -1   /* null / misaligned pointer, bad size, bad policy      */
+#define PF_ERR_CAPACITY      -2   /* a head's pool region or max_sel cannot hold the result */
+#define PF_ERR_UNSUPPORTED   -3   /* head_dim / dtype the kernels do not implement        */
+#define PF_ERR_HIP           -4   /* a HIP runtime call or kernel launch failed           */
+
+/* head types: the three head sets of Sec. 4.1 (mutually exclusive, covering) */
+#define PF_ANCHOR 0
+#define PF_WAVE   1
+#define PF_VEIL   2
+/* Anchor modes */
+#define PF_MODE_ALL     0   /* keep every intermediate frame                               */
+#define PF_MODE_STRIDED 1   /* adaptive strided sliding window, Sec. 4.2 Eq. 4             */
+#define PF_MODE_TOPK    2   /* the cap best-scored intermediate frames (static scores)     */
+
+/*
+ * Cache policy of one head (Sec. 4.2).  All heads share the meaning of `sink`
+ * (S, first frames of the video) and `recent` (R, newest frames), which are
+ * always attended; the type-specific rule acts on the intermediate frames
+ * S .. T-R-1:
+ *   Anchor/ALL      all of them;
+ *   Anchor/STRIDED  if more than cap: the cap window centres
+ *                   S + (t'-1) - floor(i*t'/cap) - floor(t'/(2cap)), i=0..cap-1,
+ *                   t' = number of intermediate frames (Eq. 4 in 0-based ids);
+ *   Anchor/TOPK     the cap frames with the largest score given at append time
+ *                   (ties: smaller id first);
+ *   Wave            T - i*period, i = 1,2,... (Eq. 5 / Observation 2), the cap
+ *                   nearest ones if cap > 0;
+ *   Veil            none.
+ * cap = 0 means unlimited.  `slots` is the capacity, in frames, of this head's
+ * region of the pool.
+ */
+typedef struct pf_head_policy {
+  int32_t type;      /* PF_ANCHOR | PF_WAVE | PF_VEIL */
+  int32_t mode;      /* PF_MODE_*, Anchor only (0 otherwise) */
+  int32_t sink;      /* S >= 0 */
+  int32_t recent;    /* R >= 0 */
+  int32_t cap;       /* Cap >= 0, 0 = unlimited */
+  int32_t period;    /* P >= 1, Wave only (ignored otherwise) */
+  int32_t slots;     /* >= 1 */
+  int32_t reserved;  /* must be 0 */
+} pf_head_policy;
+
+/*
+ * The per-head ragged KV pool: the retained candidate history H(t) of Sec. 2.2
+ * stored as the flattened, unpadded layout of Sec. 4.3.  Head h owns pool
+ * slots slot_base[h] .. slot_base[h+1]-1; its resident frames sit in the first
+ * n_frames[h] of them in ascending frame id (left-packed), the rest are free
+ * (frame_ids = -1, frame_score = 0, K/V bytes unspecified).
+ * Slot s holds tokens_per_frame x head_dim elements at
+ * k_pool + s*tokens_per_frame*head_dim (same for v_pool).
+ */
+typedef struct pf_pool {
+  int32_t n_heads;
+  int32_t head_dim;               /* 64 or 128 */
+  int32_t tokens_per_frame;       /* >= 1 */
+  int32_t dtype;                  /* 0 = bfloat16 */
+  int64_t total_slots;            /* sum of policy[h].slots */
+  void *k_pool;                   /* dev [total_slots][tokens_per_frame][head_dim], 16-byte aligned */
+  void *v_pool;                   /* dev, same shape */
+  const pf_head_policy *policy_host; /* host [n_heads] */
+  const pf_head_policy *policy_dev;  /* dev  [n_heads], same contents */
+  const int32_t *slot_base;       /* dev [n_heads+1], exclusive prefix sum of slots */
+  int32_t *n_frames;              /* dev [n_heads]      resident frames per head */
+  int32_t *frame_ids;             /* dev [total_slots]  global frame id, -1 = free */
+  float   *frame_score;           /* dev [total_slots]  score of the resident frame, 0 = free */
+  int32_t *T_dev;                 /* dev [1]            frames appended so far */
+  int32_t *sync;                  /* dev [n_heads]      library scratch, zeroed by pf_pool_reset */
+  int32_t T_host;                 /* [lib] host mirror of *T_dev (no device read-back needed) */
+  int32_t reserved;
+} pf_pool;
+
+/*
+ * The frame index of one layer: for each head the selected subset I(t) of the
+ * pool (Sec. 2.2), as ascending frame ids and the pool slots that hold them,
+ * plus the boundary indices of the flattened ragged history (Sec. 4.3):
+ * cu_seqlens[0] = 0, cu_seqlens[h+1] = cu_seqlens[h] + sel_count[h]*tokens_per_frame.
+ * The key/value sequence head h attends to is its selected frames in this
+ * order followed by the current chunk: Lkv[h] = cu_seqlens[h+1]-cu_seqlens[h] + q_tokens.
+ * `work` is library scratch (launch plan of pf_ragged_attn_fwd, private format).
+ */
+typedef struct pf_index {
+  int32_t max_sel;                /* row length of sel_frames / sel_slots */
+  int32_t seg_tiles;              /* tuning: key tiles per work item, 0 = library default */
+  int32_t *sel_count;             /* dev [n_heads] */
+  int32_t *sel_frames;            /* dev [n_heads][max_sel], unused entries -1 */
+  int32_t *sel_slots;             /* dev [n_heads][max_sel], global pool slots, unused -1 */
+  int32_t *cu_seqlens;            /* dev [n_heads+1] */
+  void *work;                     /* dev, >= pf_index_work_bytes(), 16-byte aligned */
+  size_t work_bytes;
+  /* [lib] host-side description of the plan written by pf_build_index */
+  int32_t q_tokens;               /* chunk length the plan was built for */
+  int32_t T_built;                /* pool->T_host at build time */
+  int32_t n_blocks;               /* workgroups of the attention launch */
+  int32_t n_partials;             /* partial-result slots the launch uses */
+  int32_t variant;                /* kernel variant the plan was built for */
+  int32_t reserved;
+} pf_index;
+
+/* ---- sizes (host only, no device access) -------------------------------- */
+
+/* Bytes of pf_index.work needed for a pool with these policies, for any T the
+ * pool's slot capacities allow.  0 on a bad argument. */
+size_t pf_index_work_bytes(const pf_pool *pool, int q_tokens);
+
+/* Upper bound of the workspace pf_ragged_attn_fwd needs for this pool and
+ * chunk length (partial results of heads whose keys are split over several
+ * workgroups), for any T the slot capacities allow.  Never 0 for valid input. */
+size_t pf_attn_workspace_bytes(const pf_pool *pool, int q_tokens);
+
+/* ---- host-side planning helpers (no device access) ---------------------- */
+
+/* Number of frames head `pol` attends to / the pool retains when the history
+ * has T frames.  Both are functions of T and the policy alone (for TOPK the
+ * scores decide WHICH frames, not how many).  Negative = PF_ERR_INVALID_ARG. */
+int pf_selected_count(const pf_head_policy *pol, int T);
+int pf_retained_count(const pf_head_policy *pol, int T);
+
+/* ---- the hot path -------------------------------------------------------- */
+
+/* Empty the pool: T = 0, n_frames = 0, frame_ids = -1, frame_score = 0,
+ * sync = 0.  K/V bytes are left as they are. */
+int pf_pool_reset(pf_pool *pool, void *stream);
+
+/*
+ * Write-back of Sec. 2.2: append n_new frames (ids T .. T+n_new-1) to every
+ * head, evict what the head's policy no longer retains and left-pack the
+ * survivors (stable: ascending frame id), in one launch for all heads
+ * (the batched workspace packing of Sec. 4.3).
+ *   k_new, v_new  dev [n_heads][n_new][tokens_per_frame][head_dim], 16-byte aligned
+ *   scores        dev [n_heads][n_new] float, or NULL (= 0) -- used by Anchor/TOPK
+ * PF_ERR_CAPACITY if any head would hold more than its `slots` frames after
+ * eviction; the pool is then untouched.  On success pool->T_host += n_new.
+ */
+int pf_cache_append(pf_pool *pool, const void *k_new, const void *v_new,
+                    int n_new, const float *scores, void *stream);
+
+/*
+ * Select every head's frames for the chunk that starts at frame id T
+ * (Sec. 4.2 policies), map them to pool slots, write cu_seqlens (Sec. 4.3) and
+ * the private launch plan of pf_ragged_attn_fwd for a chunk of q_tokens tokens.
+ * PF_ERR_CAPACITY if a head selects more than max_sel frames.
+ */
+int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens, void *stream);
+
+/*
+ * Ragged-cache attention (Sec. 4.3) = Eq. 1 evaluated per head over that
+ * head's key/value sequence [selected history frames || current chunk]:
+ *   out[h,i,:] = sum_j softmax_j( scale * q[h,i,:].K_h[j,:] ) * V_h[j,:]
+ * Every chunk token sees all chunk tokens and all selected history (no mask
+ * inside the chunk).  bf16 inputs, fp32 accumulation, bf16 output; ONE launch
+ * for all heads of the layer.
+ *   q, k_cur, v_cur, out  dev [n_heads][q_tokens][head_dim] bf16, 16-byte aligned
+ *   softmax_scale         0 = 1/sqrt(head_dim)
+ *   workspace             dev, >= pf_attn_workspace_bytes(), 16-byte aligned
+ * `index` must have been built for this q_tokens and the pool's current T.
+ */
+int pf_ragged_attn_fwd(const pf_pool *pool, const pf_index *index,
+                       const void *q, const void *k_cur, const void *v_cur, void *out,
+                       int q_tokens, float softmax_scale,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Human-readable text for a status code (static storage). */
+const char *pf_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PF_H */

@@ -1,0 +1,129 @@
+"""Seeded synthetic inputs shared by the HIP path's tests, the oracle's tests and the benchmark.
+
+This module holds shapes, policy tables and random tensors only -- none of the
+method's arithmetic (no frame selection, no attention).  The workloads stand in
+for the paper's evaluation inputs (a Wan-1.3B-class autoregressive video DiT:
+30 layers x 12 heads, head_dim 128, 1560 tokens per latent frame, 3-frame
+chunks), which need model weights and prompt sets that are not available here.
+"""
+from collections import namedtuple
+
+import torch
+
+ANCHOR, WAVE, VEIL = 0, 1, 2
+MODE_ALL, MODE_STRIDED, MODE_TOPK = 0, 1, 2
+
+HeadPolicy = namedtuple("HeadPolicy", "type mode sink recent cap period slots")
+
+Workload = namedtuple("Workload", "name n_layers n_heads head_dim tokens_per_frame chunk_frames history_frames")
+
+WORKLOADS = {
+    # tiny case: 1 Anchor (all 12), 1 Wave (every 3rd), 2 Veil (frame 0 + last 2)
+    "c1_tiny": Workload("c1_tiny", 1, 4, 64, 16, 3, 12),
+    # one layer at model shape: 4 Anchor (all 18), 4 Wave (every 2nd), 4 Veil (frame 0 + last 3)
+    "c2_layer": Workload("c2_layer", 1, 12, 128, 1560, 3, 18),
+    # full 30-layer denoising step, 57 history frames, types drawn 40/30/30
+    "c3_step": Workload("c3_step", 30, 12, 128, 1560, 3, 57),
+    # skewed stress case: 8 Anchor keep all 60, 32 Veil keep 4
+    "c4_skew": Workload("c4_skew", 1, 40, 128, 1560, 3, 60),
+    # streaming rollout: 1-frame chunks, 40 chunks, 4 denoising passes per chunk
+    "c5_stream": Workload("c5_stream", 30, 12, 128, 1560, 1, 40),
+}
+
+
+def _cpu_gen(seed):
+    g = torch.Generator(device="cpu")
+    g.manual_seed(int(seed))
+    return g
+
+
+def anchor_all(slots):
+    return HeadPolicy(ANCHOR, MODE_ALL, 0, 0, 0, 1, slots)
+
+
+def anchor_strided(cap, slots, sink=0, recent=0):
+    return HeadPolicy(ANCHOR, MODE_STRIDED, sink, recent, cap, 1, slots)
+
+
+def anchor_topk(cap, slots, sink=0, recent=0):
+    return HeadPolicy(ANCHOR, MODE_TOPK, sink, recent, cap, 1, slots)
+
+
+def wave(period, slots, cap=0, sink=0, recent=0):
+    return HeadPolicy(WAVE, 0, sink, recent, cap, period, slots)
+
+
+def veil(sink, recent, slots=None):
+    return HeadPolicy(VEIL, 0, sink, recent, 0, 1, slots if slots is not None else sink + recent)
+
+
+def drawn_policies(n_heads, seed, max_frames, topk_cap=18, veil_recent=3):
+    """Head types drawn 40/30/30 (Anchor/Wave/Veil) from the seed; Anchor = TOPK with ``topk_cap``,
+    Wave period uniform in {2,3,4} and uncapped, Veil = 1 sink + ``veil_recent`` adjacent frames."""
+    g = _cpu_gen(seed)
+    u = torch.rand(n_heads, generator=g)
+    periods = torch.randint(2, 5, (n_heads,), generator=g)
+    pols = []
+    for h in range(n_heads):
+        if u[h] < 0.4:
+            pols.append(anchor_topk(topk_cap, min(max_frames, topk_cap)))
+        elif u[h] < 0.7:
+            pols.append(wave(int(periods[h]), max_frames))
+        else:
+            pols.append(veil(1, veil_recent))
+    return pols
+
+
+def policies(workload, layer=0, extra_frames=0):
+    """Policy table of one layer.  ``extra_frames`` adds pool capacity beyond the workload's history."""
+    w = WORKLOADS[workload] if isinstance(workload, str) else workload
+    cap_frames = w.history_frames + extra_frames
+    if w.name == "c1_tiny":
+        return [anchor_all(cap_frames), wave(3, cap_frames), veil(1, 2), veil(1, 2)]
+    if w.name == "c2_layer":
+        return [anchor_all(cap_frames)] * 4 + [wave(2, cap_frames)] * 4 + [veil(1, 3)] * 4
+    if w.name == "c4_skew":
+        return [anchor_all(cap_frames)] * 8 + [veil(1, 3)] * 32
+    if w.name in ("c3_step", "c5_stream"):
+        return drawn_policies(w.n_heads, 7000 + layer, cap_frames)
+    raise KeyError(w.name)
+
+
+def paper_default_policies(n_heads, seed, max_frames, wave_period=6):
+    """The paper's own hyper-parameters (experimental setup): sink 3, forced recent 4,
+    capacities Anchor/Wave/Veil 4/4/2 (Veil without merging keeps sink + recent only)."""
+    g = _cpu_gen(seed)
+    u = torch.rand(n_heads, generator=g)
+    pols = []
+    for h in range(n_heads):
+        if u[h] < 0.4:
+            pols.append(anchor_strided(4, max_frames, sink=3, recent=4))
+        elif u[h] < 0.7:
+            pols.append(wave(wave_period, min(max_frames, 3 + 4 + 5 * wave_period), cap=4, sink=3, recent=4))
+        else:
+            pols.append(veil(3, 4))
+    return pols
+
+
+def randn_bf16(shape, seed, device="cpu", std=1.0):
+    """Seeded N(0, std^2) tensor rounded to bfloat16."""
+    if str(device).startswith("cuda"):
+        g = torch.Generator(device=device)
+        g.manual_seed(int(seed))
+        x = torch.randn(shape, generator=g, device=device, dtype=torch.float32)
+    else:
+        x = torch.randn(shape, generator=_cpu_gen(seed), dtype=torch.float32)
+    if std != 1.0:
+        x = x * std
+    return x.to(torch.bfloat16)
+
+
+def frame_scores(n_heads, n_frames, seed, device="cpu"):
+    """Seeded U(0,1) float32 scores, one per (head, appended frame)."""
+    s = torch.rand((n_heads, n_frames), generator=_cpu_gen(seed), dtype=torch.float32)
+    return s.to(device)
+
+
+def bits(t):
+    """bfloat16 tensor -> numpy uint16 bit patterns (host copy)."""
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view("uint16")

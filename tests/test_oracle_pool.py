@@ -1,0 +1,95 @@
+"""Pins of the pool oracle (oracle/pool.py): streaming == batch, content identity, layout invariants."""
+import numpy as np
+import pytest
+
+from oracle import policy as P
+from oracle.pool import PoolOracle, CapacityError
+from paper_2605_13111_amd import synth
+
+
+def _frames(H, n, tpf, D, first_id):
+    """Frame f of head h is filled with a value that encodes (h, f): content identity is checkable."""
+    k = np.zeros((H, n, tpf, D), np.uint16)
+    v = np.zeros((H, n, tpf, D), np.uint16)
+    for h in range(H):
+        for j in range(n):
+            k[h, j] = (h * 1000 + first_id + j) % 65536
+            v[h, j] = (h * 1000 + first_id + j + 500) % 65536
+    return k, v
+
+
+def _mixed_policies(max_frames):
+    return [synth.anchor_all(max_frames), synth.anchor_topk(5, 5), synth.anchor_topk(4, 9, sink=2, recent=3),
+            synth.wave(3, max_frames), synth.wave(2, 16, cap=3, sink=1, recent=2), synth.veil(1, 3),
+            synth.veil(3, 4), synth.anchor_strided(4, max_frames, sink=3, recent=4)]
+
+
+@pytest.mark.parametrize("chunks", [[1] * 40, [3] * 14, [2, 1, 5, 3, 1, 1, 4, 7, 1, 2, 6, 3]])
+def test_streaming_equals_batch_and_content_identity(chunks):
+    tpf, D = 3, 4
+    total = sum(chunks)
+    pols = _mixed_policies(total)
+    H = len(pols)
+    rng = np.random.default_rng(1)
+    scores = (rng.integers(0, 40, size=(H, total)) / 8).astype(np.float32)      # ties on purpose
+    pool = PoolOracle(pols, tpf, D)
+    T = 0
+    for n_new in chunks:
+        k, v = _frames(H, n_new, tpf, D, T)
+        pool.append(k, v, scores[:, T:T + n_new])
+        T += n_new
+        assert pool.T == T
+        n_frames, frame_ids, frame_score = pool.tables()
+        base = pool.slot_base()
+        for h, pol in enumerate(pols):
+            ids = frame_ids[base[h]:base[h + 1]]
+            n = n_frames[h]
+            # one retention pass over the whole history gives the same resident set
+            want = P.retained_frames(pol, T, list(range(T)), {f: scores[h, f] for f in range(T)})
+            assert ids[:n].tolist() == want
+            assert (ids[n:] == -1).all() and (frame_score[base[h] + n:base[h + 1]] == 0).all()
+            assert n <= pol.slots
+            assert np.array_equal(frame_score[base[h]:base[h] + n], scores[h, want])
+            if pol.type == synth.VEIL and T >= pol.sink + pol.recent:
+                assert n == pol.sink + pol.recent                                # Veil steady state
+        for slot, K, V in pool.resident_kv():
+            h = max(i for i in range(H) if base[i] <= slot)
+            f = frame_ids[slot]
+            assert (K == (h * 1000 + f) % 65536).all() and (V == (h * 1000 + f + 500) % 65536).all()
+
+
+def test_index_from_the_pool():
+    w = synth.WORKLOADS["c1_tiny"]
+    pols = synth.policies("c1_tiny")
+    pool = PoolOracle(pols, w.tokens_per_frame, w.head_dim)
+    T = 0
+    for _ in range(4):
+        k, v = _frames(4, 3, w.tokens_per_frame, w.head_dim, T)
+        pool.append(k, v)
+        T += 3
+    sel_count, sel_frames, sel_slots, cu = pool.build_index(max_sel=12)
+    assert sel_count.tolist() == [12, 4, 3, 3]
+    assert sel_frames[1, :4].tolist() == [0, 3, 6, 9] and (sel_frames[1, 4:] == -1).all()
+    assert sel_frames[2, :3].tolist() == [0, 10, 11]
+    base = pool.slot_base()
+    assert base == [0, 12, 24, 27, 30]
+    # Wave keeps everything resident (uncapped) so frame f sits in slot f; Veil packs {0,10,11} into 3 slots
+    assert sel_slots[1, :4].tolist() == [12 + 0, 12 + 3, 12 + 6, 12 + 9]
+    assert sel_slots[2, :3].tolist() == [24, 25, 26] and sel_slots[3, :3].tolist() == [27, 28, 29]
+    assert cu.tolist() == [0, 192, 256, 304, 352]
+    Kb, Vb = pool.head_kv(2, [0, 10, 11])
+    assert Kb.shape == (48, 64) and (Kb[:16] == 2000).all() and (Kb[16:32] == 2010).all() and (Vb[32:] == 2511).all()
+
+
+def test_capacity_error_leaves_the_pool_untouched():
+    pols = [synth.anchor_all(4), synth.veil(1, 2)]
+    pool = PoolOracle(pols, 2, 2)
+    k, v = _frames(2, 3, 2, 2, 0)
+    pool.append(k, v)
+    before = [t.copy() for t in pool.tables()]
+    k, v = _frames(2, 2, 2, 2, 3)
+    with pytest.raises(CapacityError):
+        pool.append(k, v)                       # Anchor/ALL would need 5 > 4 slots
+    assert pool.T == 3
+    for a, b in zip(before, pool.tables()):
+        assert np.array_equal(a, b)
