@@ -1,0 +1,226 @@
+// Per-head ragged KV pool: reset and append / evict / left-pack (the write-back of Sec. 2.2 done as
+// the batched packing of Sec. 4.3: one launch for all heads, no per-head host loop).
+//
+// Hazard-free in-place packing.  Survivors keep their ascending order, so a frame only ever moves to
+// a lower slot, and the destination of the k-th kept frame can only coincide with the source of an
+// EARLIER kept frame.  Every thread owns a fixed byte range of the frame payload and walks the kept
+// frames in order, so all reads and writes of one byte range are issued by one thread in program
+// order: no synchronisation between workgroups is needed and the copy streams at HBM speed.
+#include "pf_internal.h"
+
+constexpr int POOL_THREADS = 256;
+constexpr int POOL_UNITS_PER_THREAD = 4;                    // 16-byte units per thread per frame
+constexpr int POOL_CHUNK_UNITS = POOL_THREADS * POOL_UNITS_PER_THREAD;
+constexpr int POOL_MAX_CAND = 2048;                         // resident + new frames of one head
+constexpr int POOL_MOVE_BATCH = 4;                          // frames in flight per thread
+
+__global__ void pf_pool_reset_kernel(int32_t *n_frames, int32_t *frame_ids, float *frame_score,
+                                     int32_t *T_dev, int32_t *sync, int n_heads, long long total_slots) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < total_slots) {
+    frame_ids[i] = -1;
+    frame_score[i] = 0.0f;
+  }
+  if (i < n_heads) {
+    n_frames[i] = 0;
+    sync[i] = 0;
+  }
+  if (i == 0) *T_dev = 0;
+}
+
+struct PoolAppendParams {
+  uint4 *k_pool, *v_pool;
+  const uint4 *k_new, *v_new;
+  const float *scores;
+  const pf_head_policy *policy;
+  const int32_t *slot_base;
+  int32_t *n_frames, *frame_ids, *T_dev, *sync;
+  float *frame_score;
+  int T, n_new, frame_units, blocks_per_head;
+};
+
+// Is candidate frame `f` (an intermediate frame of head p at history length T) kept by the type rule?
+// rank = number of intermediate candidates that beat it (TOPK only).
+__device__ __forceinline__ bool middle_kept(const pf_head_policy &p, int T, int f, int rank) {
+  if (p.type == PF_ANCHOR) return (p.mode == PF_MODE_TOPK && p.cap > 0) ? rank < p.cap : true;
+  if (p.type == PF_WAVE) return p.cap <= 0 ? true : f >= pf_wave_oldest(p, T);
+  return false;   // Veil: sink + recent only
+}
+
+__global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppendParams P) {
+  __shared__ int32_t s_id[POOL_MAX_CAND];
+  __shared__ float s_score[POOL_MAX_CAND];
+  __shared__ int32_t s_dest[POOL_MAX_CAND];     // destination slot or -1 (evicted)
+  __shared__ int32_t s_move_src[POOL_MAX_CAND]; // >= 0: resident slot, < 0: -(new index)-1
+  __shared__ int32_t s_move_dst[POOL_MAX_CAND];
+  __shared__ int32_t s_counts[2];               // kept frames, moves
+  __shared__ int32_t s_last;
+
+  const int h = blockIdx.y;
+  const bool is_v = blockIdx.z != 0;
+  const int tid = threadIdx.x;
+  const pf_head_policy pol = P.policy[h];
+  const int base = P.slot_base[h];
+  const int n_old = P.n_frames[h];
+  const int n_cand = n_old + P.n_new;
+  const int T_new = P.T + P.n_new;
+
+  for (int j = tid; j < n_cand; j += POOL_THREADS) {
+    if (j < n_old) {
+      s_id[j] = P.frame_ids[base + j];
+      s_score[j] = P.frame_score[base + j];
+    } else {
+      s_id[j] = P.T + (j - n_old);
+      s_score[j] = P.scores ? P.scores[(size_t)h * P.n_new + (j - n_old)] : 0.0f;
+    }
+  }
+  __syncthreads();
+
+  const int mid_lo = pol.sink, mid_hi = T_new - pol.recent;   // intermediate ids [mid_lo, mid_hi)
+  const bool need_rank = pol.type == PF_ANCHOR && pol.mode == PF_MODE_TOPK && pol.cap > 0;
+  for (int j = tid; j < n_cand; j += POOL_THREADS) {
+    const int f = s_id[j];
+    bool keep;
+    if (f < mid_lo || f >= mid_hi) {
+      keep = true;                                            // sink or recent
+    } else {
+      int rank = 0;
+      if (need_rank) {
+        const float sc = s_score[j];
+        for (int g = 0; g < n_cand; ++g) {
+          const int fg = s_id[g];
+          if (fg < mid_lo || fg >= mid_hi) continue;
+          const float sg = s_score[g];
+          rank += (sg > sc || (sg == sc && fg < f)) ? 1 : 0;
+        }
+      }
+      keep = middle_kept(pol, T_new, f, rank);
+    }
+    s_dest[j] = keep ? 0 : -1;
+  }
+  __syncthreads();
+  if (tid == 0) {                                             // candidates are few: serial prefix
+    int kept = 0, moves = 0;
+    for (int j = 0; j < n_cand; ++j) {
+      if (s_dest[j] < 0) continue;
+      s_dest[j] = kept;
+      if (j >= n_old || kept != j) {                          // new frame, or a survivor that shifts left
+        s_move_src[moves] = j < n_old ? j : -(j - n_old) - 1;
+        s_move_dst[moves] = kept;
+        ++moves;
+      }
+      ++kept;
+    }
+    s_counts[0] = kept;
+    s_counts[1] = moves;
+  }
+  __syncthreads();
+  const int n_kept = s_counts[0], n_moves = s_counts[1];
+
+  // ---- payload: this workgroup owns 16-byte units [u0, u0+POOL_CHUNK_UNITS) of every frame ----
+  uint4 *pool = (is_v ? P.v_pool : P.k_pool) + (size_t)base * P.frame_units;
+  const uint4 *fresh = (is_v ? P.v_new : P.k_new) + (size_t)h * P.n_new * P.frame_units;
+  const int u0 = blockIdx.x * POOL_CHUNK_UNITS + tid;
+  for (int m0 = 0; m0 < n_moves; m0 += POOL_MOVE_BATCH) {
+    uint4 r[POOL_MOVE_BATCH][POOL_UNITS_PER_THREAD];
+#pragma unroll
+    for (int b = 0; b < POOL_MOVE_BATCH; ++b) {
+      if (m0 + b >= n_moves) break;
+      const int src = s_move_src[m0 + b];
+      const uint4 *sp = src >= 0 ? pool + (size_t)src * P.frame_units : fresh + (size_t)(-src - 1) * P.frame_units;
+#pragma unroll
+      for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u) {
+        const int unit = u0 + u * POOL_THREADS;
+        if (unit < P.frame_units) r[b][u] = sp[unit];
+      }
+    }
+#pragma unroll
+    for (int b = 0; b < POOL_MOVE_BATCH; ++b) {
+      if (m0 + b >= n_moves) break;
+      uint4 *dp = pool + (size_t)s_move_dst[m0 + b] * P.frame_units;
+#pragma unroll
+      for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u) {
+        const int unit = u0 + u * POOL_THREADS;
+        if (unit < P.frame_units) dp[unit] = r[b][u];
+      }
+    }
+  }
+
+  // ---- tables: written by the last workgroup of this head to arrive, after every workgroup of the
+  // head has read the old tables (each one read them before it signals its arrival) ----
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();
+    const int arrived = atomicAdd(&P.sync[h], 1);
+    s_last = (arrived == 2 * P.blocks_per_head - 1) ? 1 : 0;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  const int slots = pol.slots;
+  for (int j = tid; j < n_cand; j += POOL_THREADS) {
+    const int d = s_dest[j];
+    if (d >= 0) {
+      P.frame_ids[base + d] = s_id[j];
+      P.frame_score[base + d] = s_score[j];
+    }
+  }
+  for (int j = n_kept + tid; j < slots && j < n_cand; j += POOL_THREADS) {   // slots freed by this append
+    P.frame_ids[base + j] = -1;
+    P.frame_score[base + j] = 0.0f;
+  }
+  if (tid == 0) {
+    P.n_frames[h] = n_kept;
+    P.sync[h] = 0;
+    if (h == 0) *P.T_dev = T_new;
+  }
+}
+
+extern "C" int pf_pool_reset(pf_pool *pool, void *stream) {
+  const int rc = pf_validate_pool(pool);
+  if (rc != PF_OK) return rc;
+  const long long n = pool->total_slots > pool->n_heads ? pool->total_slots : pool->n_heads;
+  const int threads = 256;
+  const unsigned blocks = (unsigned)((n + threads - 1) / threads);
+  hipLaunchKernelGGL(pf_pool_reset_kernel, dim3(blocks), dim3(threads), 0, (hipStream_t)stream, pool->n_frames,
+                     pool->frame_ids, pool->frame_score, pool->T_dev, pool->sync, pool->n_heads, pool->total_slots);
+  PF_HIP_CHECK(hipGetLastError());
+  pool->T_host = 0;
+  return PF_OK;
+}
+
+extern "C" int pf_cache_append(pf_pool *pool, const void *k_new, const void *v_new, int n_new,
+                               const float *scores, void *stream) {
+  const int rc = pf_validate_pool(pool);
+  if (rc != PF_OK) return rc;
+  if (!k_new || !v_new || n_new < 1) return PF_ERR_INVALID_ARG;
+  if ((((uintptr_t)k_new) & 15u) || (((uintptr_t)v_new) & 15u)) return PF_ERR_INVALID_ARG;
+  if ((long long)pool->T_host + n_new > (1ll << 30)) return PF_ERR_INVALID_ARG;
+  const int T_new = pool->T_host + n_new;
+  for (int h = 0; h < pool->n_heads; ++h) {
+    const pf_head_policy &p = pool->policy_host[h];
+    if (pf_ret_count_impl(p, T_new) > p.slots) return PF_ERR_CAPACITY;
+    if (pf_ret_count_impl(p, pool->T_host) + n_new > POOL_MAX_CAND) return PF_ERR_CAPACITY;
+  }
+  PoolAppendParams P;
+  P.k_pool = (uint4 *)pool->k_pool;
+  P.v_pool = (uint4 *)pool->v_pool;
+  P.k_new = (const uint4 *)k_new;
+  P.v_new = (const uint4 *)v_new;
+  P.scores = scores;
+  P.policy = pool->policy_dev;
+  P.slot_base = pool->slot_base;
+  P.n_frames = pool->n_frames;
+  P.frame_ids = pool->frame_ids;
+  P.frame_score = pool->frame_score;
+  P.T_dev = pool->T_dev;
+  P.sync = pool->sync;
+  P.T = pool->T_host;
+  P.n_new = n_new;
+  P.frame_units = pool->tokens_per_frame * pool->head_dim / 8;   // bf16: 8 elements per 16 bytes
+  P.blocks_per_head = pf_ceil_div(P.frame_units, POOL_CHUNK_UNITS);
+  hipLaunchKernelGGL(pf_pool_append_kernel, dim3(P.blocks_per_head, pool->n_heads, 2), dim3(POOL_THREADS), 0,
+                     (hipStream_t)stream, P);
+  PF_HIP_CHECK(hipGetLastError());
+  pool->T_host = T_new;
+  return PF_OK;
+}

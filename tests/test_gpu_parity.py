@@ -1,0 +1,167 @@
+"""GPU parity: libpf.so through its C ABI against the CPU oracle, on the same seeded inputs."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_13111_amd import binding as B
+from paper_2605_13111_amd import synth
+import gpu_common as G
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(params=[0, 1], ids=["bq128", "bq256"])
+def variant(request):
+    old = os.environ.get("PF_ATTN_VARIANT")
+    os.environ["PF_ATTN_VARIANT"] = str(request.param)
+    yield request.param
+    if old is None:
+        os.environ.pop("PF_ATTN_VARIANT", None)
+    else:
+        os.environ["PF_ATTN_VARIANT"] = old
+
+
+def test_c1_tiny_full(variant):
+    """Tiny configuration (head_dim 64, 16 tokens/frame, 12 history frames, 48-token chunk), every row."""
+    w = synth.WORKLOADS["c1_tiny"]
+    a, r = G.run_case(synth.policies("c1_tiny"), w.tokens_per_frame, w.head_dim, [3, 3, 3, 3], 48, seed=1, label="c1")
+    print("c1 max-abs %.2e rel %.2e" % (a, r))
+
+
+def _mixed(max_frames):
+    return [synth.anchor_all(max_frames), synth.anchor_topk(5, 5), synth.anchor_topk(4, 9, sink=2, recent=3),
+            synth.wave(3, max_frames), synth.wave(2, 16, cap=3, sink=1, recent=2), synth.veil(1, 3),
+            synth.veil(3, 4), synth.anchor_strided(4, max_frames, sink=3, recent=4)]
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_mixed_policies_ragged_tails_full(variant, D):
+    """All policy kinds, frame size 40 (tiles straddle frames), 100-token chunk (ragged query tile),
+    23 frames appended in uneven chunks; segments forced short so that split heads are merged."""
+    a, r = G.run_case(_mixed(23), 40, D, [1, 3, 2, 5, 1, 1, 4, 3, 3], 100, seed=2 + D, seg_tiles=16, label="mixed")
+    print("mixed D=%d max-abs %.2e rel %.2e" % (D, a, r))
+
+
+def test_peaked_logits(variant):
+    """Queries x8: softmax close to one-hot, exercises the running-max rescaling."""
+    a, r = G.run_case(_mixed(12), 48, 128, [3, 3, 3, 3], 200, seed=5, q_gain=8.0, seg_tiles=16, label="peaked")
+    print("peaked max-abs %.2e rel %.2e" % (a, r))
+
+
+def test_explicit_scale_and_small_inputs(variant):
+    """Explicit softmax scale; second reading of the one-layer workload: tensors scaled by 1/sqrt(128)."""
+    G.run_case(_mixed(9), 24, 128, [3, 3, 3], 130, seed=6, scale=0.37, label="scale")
+
+
+def test_edge_cases(variant):
+    # no history at all: the chunk attends to itself only
+    G.run_case([synth.anchor_all(4), synth.veil(1, 2), synth.wave(2, 4)], 16, 64, [], 48, seed=7, label="T=0")
+    # one query token, one frame, tokens_per_frame 1
+    G.run_case([synth.anchor_all(2), synth.veil(1, 1)], 1, 64, [1], 1, seed=8, label="single")
+    # Wave head whose period exceeds the history: selects nothing
+    G.run_case([synth.wave(7, 8), synth.anchor_all(8)], 8, 128, [3], 17, seed=9, label="empty-selection")
+    # key count an exact multiple of the tile, and one beyond
+    G.run_case([synth.anchor_all(4)], 16, 64, [3], 16, seed=10, label="64-keys")
+    G.run_case([synth.anchor_all(4)], 16, 64, [3], 17, seed=11, label="65-keys")
+
+
+def test_structured_values_reveal_the_attended_frames(variant):
+    """V of frame f is the constant f+1, chunk values are 0, Q = 0: out = sum of selected (f+1)*tpf / Lkv."""
+    dev = "cuda:0"
+    tpf, D, Lq, T = 24, 128, 72, 15
+    pols = _mixed(T)
+    H = len(pols)
+    pool = B.Pool(pols, tpf, D, device=dev)
+    B.pf_pool_reset(pool)
+    sc_all = synth.frame_scores(H, T, 77)
+    for t0 in range(0, T, 3):
+        k = synth.randn_bf16((H, 3, tpf, D), 70 + t0).to(dev)
+        v = torch.zeros((H, 3, tpf, D), dtype=torch.bfloat16, device=dev)
+        for j in range(3):
+            v[:, j] = float(t0 + j + 1)
+        B.pf_cache_append(pool, k, v, sc_all[:, t0:t0 + 3].contiguous().to(dev))
+    index = B.Index(pool, Lq, seg_tiles=16)
+    B.pf_build_index(pool, index, Lq)
+    q = torch.zeros((H, Lq, D), dtype=torch.bfloat16, device=dev)
+    kc = synth.randn_bf16((H, Lq, D), 78).to(dev)
+    vc = torch.zeros((H, Lq, D), dtype=torch.bfloat16, device=dev)
+    out = torch.empty_like(q)
+    ws = torch.empty(1 << 26, dtype=torch.uint8, device=dev)
+    B.pf_ragged_attn_fwd(pool, index, q, kc, vc, out, ws)
+    torch.cuda.synchronize()
+    from oracle import policy as OP
+    for h, pol in enumerate(pols):
+        sel = OP.selected_frames(pol, T, {f: sc_all[h, f].item() for f in range(T)})
+        want = sum((f + 1) * tpf for f in sel) / (len(sel) * tpf + Lq)
+        got = out[h].float().cpu().numpy()
+        assert np.abs(got - want).max() <= 2 ** -8 * max(want, 1.0), (h, want, got.min(), got.max())
+
+
+def test_capacity_error_on_device_leaves_pool_untouched():
+    dev = "cuda:0"
+    pols = [synth.anchor_all(4), synth.veil(1, 2)]
+    pool = B.Pool(pols, 8, 64, device=dev)
+    B.pf_pool_reset(pool)
+    k = synth.randn_bf16((2, 3, 8, 64), 1).to(dev)
+    B.pf_cache_append(pool, k, k)
+    torch.cuda.synchronize()
+    before = [t.clone() for t in (pool.n_frames, pool.frame_ids, pool.frame_score, pool.T_dev, pool.k_pool)]
+    with pytest.raises(B.PfError) as e:
+        B.pf_cache_append(pool, k[:, :2].contiguous(), k[:, :2].contiguous())
+    assert e.value.status == B.PF_ERR_CAPACITY and pool.T == 3
+    torch.cuda.synchronize()
+    for a, b in zip(before, (pool.n_frames, pool.frame_ids, pool.frame_score, pool.T_dev, pool.k_pool)):
+        assert torch.equal(a, b)
+
+
+def test_streaming_pool_and_index_at_model_frame_size():
+    """1560-token frames, head_dim 128, 1-frame chunks, drawn policies (TOPK / Wave / Veil): pool tables and
+    payload bit-exact after every append, index bit-exact at several history lengths."""
+    from oracle.pool import PoolOracle
+    dev = "cuda:0"
+    H, tpf, D, n_chunks = 6, 1560, 128, 24
+    pols = [synth.anchor_topk(6, 6), synth.wave(3, n_chunks), synth.veil(1, 3), synth.anchor_topk(4, 8, sink=1, recent=3),
+            synth.wave(2, 12, cap=3, sink=1, recent=2), synth.anchor_all(n_chunks)]
+    pool_o = PoolOracle(pols, tpf, D)
+    pool_g = B.Pool(pols, tpf, D, device=dev)
+    B.pf_pool_reset(pool_g)
+    index = B.Index(pool_g, tpf)
+    for c in range(n_chunks):
+        k = synth.randn_bf16((H, 1, tpf, D), 3000 + 2 * c)
+        v = synth.randn_bf16((H, 1, tpf, D), 3001 + 2 * c)
+        sc = synth.frame_scores(H, 1, 4000 + c)
+        pool_o.append(synth.bits(k), synth.bits(v), sc.numpy())
+        B.pf_cache_append(pool_g, k.to(dev), v.to(dev), sc.to(dev))
+        if c % 4 == 3 or c < 3:
+            G.check_pool(pool_g, pool_o)
+            B.pf_build_index(pool_g, index, tpf)
+            G.check_index(index, pool_o)
+
+
+def _full_size(name, layer, rows_n, seed, variant_label):
+    w = synth.WORKLOADS[name]
+    pols = synth.policies(name, layer=layer)
+    Lq = w.chunk_frames * w.tokens_per_frame
+    chunks = [w.chunk_frames] * (w.history_frames // w.chunk_frames)
+    rows = G.sample_rows(Lq, rows_n, seed, extra=(1559, 1560, 3119, 3120))
+    a, r = G.run_case(pols, w.tokens_per_frame, w.head_dim, chunks, Lq, seed=seed, rows=rows,
+                      check_every_append=False, label=name)
+    print("%s %s sampled rows: max-abs %.2e rel %.2e" % (name, variant_label, a, r))
+
+
+def test_c2_one_layer_sampled_rows(variant):
+    """One layer at model shape (12 heads, 4680-token chunk, 18 history frames) in the bench's launch
+    configuration; 64 sampled query rows per head against the oracle."""
+    _full_size("c2_layer", 0, 64, 21, variant)
+
+
+def test_c3_layer_sampled_rows():
+    """One layer of the 30-layer step (57 history frames, drawn policies incl. TOPK-18)."""
+    _full_size("c3_step", 3, 64, 22, "default")
+
+
+def test_c4_skew_sampled_rows():
+    """Skewed case: 8 Anchor heads keep all 60 frames, 32 Veil heads keep 4."""
+    _full_size("c4_skew", 0, 64, 23, "default")

@@ -1,0 +1,115 @@
+"""CPU-only tests of libpf.so: exported symbols, closed-form counts against the oracle, and argument
+validation (all rejected before any device access, so fake device pointers are enough)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import policy as P
+from paper_2605_13111_amd import binding as B
+from paper_2605_13111_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+pytestmark = pytest.mark.skipif(not os.path.exists(B.LIB_PATH), reason="libpf.so not built")
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "pf.h")).read()
+    declared = set(re.findall(r"\b(pf_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def _policies():
+    out = []
+    for S in (0, 1, 3):
+        for R in (0, 2, 4):
+            out.append(synth.HeadPolicy(synth.ANCHOR, synth.MODE_ALL, S, R, 0, 1, 100))
+            out.append(synth.HeadPolicy(synth.VEIL, 0, S, R, 0, 1, 100))
+            for cap in (0, 2, 4, 18):
+                out.append(synth.HeadPolicy(synth.ANCHOR, synth.MODE_STRIDED, S, R, cap, 1, 100))
+                out.append(synth.HeadPolicy(synth.ANCHOR, synth.MODE_TOPK, S, R, cap, 1, 100))
+                for period in (1, 2, 3, 6):
+                    out.append(synth.HeadPolicy(synth.WAVE, 0, S, R, cap, period, 100))
+    return out
+
+
+def test_closed_form_counts_match_the_oracle():
+    """The host sizes launches and checks capacity from closed-form counts; they must equal the length of
+    the oracle's frame lists for every policy and history length."""
+    score = {f: float((f * 7919) % 97) for f in range(100)}
+    for pol in _policies():
+        for T in range(0, 90):
+            sc = {f: score[f] for f in range(T)}
+            assert B.pf_selected_count(pol, T) == len(P.selected_frames(pol, T, sc)), (pol, T)
+            assert B.pf_retained_count(pol, T) == len(P.retained_frames(pol, T, list(range(T)), sc)), (pol, T)
+
+
+def test_count_helpers_reject_bad_policies():
+    bad = synth.HeadPolicy(7, 0, 0, 0, 0, 1, 4)
+    assert B.pf_selected_count(bad, 3) == B.PF_ERR_INVALID_ARG
+    assert B.pf_retained_count(synth.HeadPolicy(synth.WAVE, 0, 0, 0, 0, 0, 4), 3) == B.PF_ERR_INVALID_ARG
+    assert B.pf_selected_count(synth.anchor_all(4), -1) == B.PF_ERR_INVALID_ARG
+
+
+def _fake_pool(policies, tpf=16, D=64):
+    """A pf_pool whose device pointers are fake but non-null and aligned: good enough for every check
+    that happens before a kernel launch."""
+    H = len(policies)
+    host = (B.pf_head_policy * H)(*[B.make_policy(p) for p in policies])
+    total = sum(p.slots for p in policies)
+    fake = 0x1000
+    pool = B.pf_pool(H, D, tpf, 0, total, fake, fake, ctypes.cast(host, ctypes.POINTER(B.pf_head_policy)), fake,
+                     fake, fake, fake, fake, fake, fake, 0, 0)
+    pool._keep = host
+    return pool
+
+
+def test_argument_validation_without_a_device():
+    lib = B.lib()
+    pols = [synth.anchor_all(4), synth.veil(1, 2)]
+    pool = _fake_pool(pols)
+    fake = ctypes.c_void_p(0x1000)
+    null = ctypes.c_void_p(0)
+    # sizes
+    assert lib.pf_index_work_bytes(ctypes.byref(pool), 48) > 0
+    assert lib.pf_attn_workspace_bytes(ctypes.byref(pool), 48) > 0
+    assert lib.pf_index_work_bytes(ctypes.byref(pool), 0) == 0
+    assert lib.pf_index_work_bytes(None, 48) == 0
+    # append: bad arguments
+    assert lib.pf_cache_append(None, fake, fake, 1, null, null) == B.PF_ERR_INVALID_ARG
+    assert lib.pf_cache_append(ctypes.byref(pool), null, fake, 1, null, null) == B.PF_ERR_INVALID_ARG
+    assert lib.pf_cache_append(ctypes.byref(pool), fake, fake, 0, null, null) == B.PF_ERR_INVALID_ARG
+    assert lib.pf_cache_append(ctypes.byref(pool), ctypes.c_void_p(0x1004), fake, 1, null, null) == B.PF_ERR_INVALID_ARG
+    # append: Anchor/ALL has 4 slots, 5 frames do not fit -> capacity error, host mirror untouched
+    assert lib.pf_cache_append(ctypes.byref(pool), fake, fake, 5, null, null) == B.PF_ERR_CAPACITY
+    assert pool.T_host == 0
+    # unsupported head_dim / dtype, inconsistent total_slots, bad policy
+    p2 = _fake_pool(pols, D=96)
+    assert lib.pf_cache_append(ctypes.byref(p2), fake, fake, 1, null, null) == B.PF_ERR_UNSUPPORTED
+    p3 = _fake_pool(pols)
+    p3.total_slots = 99
+    assert lib.pf_pool_reset(ctypes.byref(p3), null) == B.PF_ERR_INVALID_ARG
+    p4 = _fake_pool([synth.HeadPolicy(synth.WAVE, 0, 0, 0, 0, 0, 4)])
+    assert lib.pf_pool_reset(ctypes.byref(p4), null) == B.PF_ERR_INVALID_ARG
+    # index: null struct, max_sel too small for what the policies select at T = 4
+    assert lib.pf_build_index(ctypes.byref(pool), None, 48, null) == B.PF_ERR_INVALID_ARG
+    pool.T_host = 4
+    idx = B.pf_index(2, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 20, 0, 0, 0, 0, 0, 0)
+    assert lib.pf_build_index(ctypes.byref(pool), ctypes.byref(idx), 48, null) == B.PF_ERR_CAPACITY
+    idx = B.pf_index(8, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 64, 0, 0, 0, 0, 0, 0)   # work buffer too small
+    assert lib.pf_build_index(ctypes.byref(pool), ctypes.byref(idx), 48, null) == B.PF_ERR_CAPACITY
+    # attention: stale index (built for another T / q_tokens) and null tensors
+    idx = B.pf_index(8, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 20, 48, 3, 8, 0, 0, 0)
+    assert lib.pf_ragged_attn_fwd(ctypes.byref(pool), ctypes.byref(idx), fake, fake, fake, fake, 48, 0.0, null, 0,
+                                  null) == B.PF_ERR_INVALID_ARG
+    idx.T_built = 4
+    assert lib.pf_ragged_attn_fwd(ctypes.byref(pool), ctypes.byref(idx), null, fake, fake, fake, 48, 0.0, null, 0,
+                                  null) == B.PF_ERR_INVALID_ARG
+    assert lib.pf_ragged_attn_fwd(ctypes.byref(pool), ctypes.byref(idx), fake, fake, fake, fake, 32, 0.0, null, 0,
+                                  null) == B.PF_ERR_INVALID_ARG
+    assert B.lib().pf_status_string(B.PF_ERR_CAPACITY) == b"capacity exceeded"
