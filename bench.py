@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the ragged-cache attention path on one MI355X.
+
+Workload (default): the full 30-layer denoising step at Wan-1.3B shape -- 30 layers x 12 heads, head_dim 128,
+1560 tokens/frame, a 3-frame query chunk (4680 tokens) and 57 history frames; head types drawn 40/30/30 from the
+seed (Anchor = 18 best-scored frames, Wave period 2-4, Veil = first + last 3 frames).  Every layer's pool is filled
+through pf_cache_append (19 appends of 3 frames).  One timed "step" = for each of the 30 layers: pf_build_index +
+pf_ragged_attn_fwd, launched back to back on one stream (layer l+1 depends on layer l in a real model).
+
+The value is effective TFLOP/s over retained keys: sum over (layer, head) of 4*Lq*Lkv*D / step time.
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3_step", choices=["c2_layer", "c3_step", "c4_skew"])
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
+    ap.add_argument("--cpu-rows", type=int, default=192, help="query rows per head of layer 0 timed on the CPU oracle")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    from paper_2605_13111_amd import binding as B
+    from paper_2605_13111_amd import synth
+    B.lib()                                           # fail loudly if libpf.so is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    n_layers = args.layers or w.n_layers
+    H, D, tpf = w.n_heads, w.head_dim, w.tokens_per_frame
+    Lq = w.chunk_frames * tpf
+    T = w.history_frames
+    frame_bytes = tpf * D * 2
+
+    # ---------------------------------------------------------------- setup: pools filled through the library
+    layers = []
+    hist0 = None
+    append_ms, append_bytes = [], []
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    for layer in range(n_layers):
+        pols = synth.policies(w.name, layer=layer)
+        pool = B.Pool(pols, tpf, D, device=dev)
+        B.pf_pool_reset(pool)
+        keep_k, keep_v, keep_s = [], [], []
+        for ci, t0 in enumerate(range(0, T, w.chunk_frames)):
+            n_new = min(w.chunk_frames, T - t0)
+            seed = 100000 * (layer + 1) + 10 * ci
+            k_new = synth.randn_bf16((H, n_new, tpf, D), seed, device=dev)
+            v_new = synth.randn_bf16((H, n_new, tpf, D), seed + 1, device=dev)
+            sc = synth.frame_scores(H, n_new, seed + 2, device=dev)
+            last = t0 + n_new >= T
+            if last:                                   # time the append that brings the pool to T frames
+                ids_before = pool.frame_ids.cpu().numpy().copy()
+                e0, e1 = ev(), ev()
+                e0.record()
+            B.pf_cache_append(pool, k_new, v_new, sc)
+            if last:
+                e1.record()
+                torch.cuda.synchronize()
+                ids_after = pool.frame_ids.cpu().numpy()
+                moved = int(((ids_after != ids_before) & (ids_after >= 0) & (ids_after < t0)).sum())
+                append_ms.append(e0.elapsed_time(e1))
+                append_bytes.append(2 * 2 * frame_bytes * (H * n_new + moved))   # K and V, read + write
+            if layer == 0 and not args.no_cpu:
+                keep_k.append(k_new.cpu())
+                keep_v.append(v_new.cpu())
+                keep_s.append(sc.cpu())
+        if layer == 0 and not args.no_cpu:
+            hist0 = (pols, keep_k, keep_v, keep_s)
+        index = B.Index(pool, Lq)
+        q = synth.randn_bf16((H, Lq, D), 900000 + layer, device=dev)
+        k_cur = synth.randn_bf16((H, Lq, D), 910000 + layer, device=dev)
+        v_cur = synth.randn_bf16((H, Lq, D), 920000 + layer, device=dev)
+        out = torch.empty_like(q)
+        layers.append((pool, index, q, k_cur, v_cur, out))
+    ws_bytes = max(B.pf_attn_workspace_bytes(L[0], Lq) for L in layers)
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)     # layers run one after another: shared
+    torch.cuda.synchronize()
+
+    def step(events=None):
+        for (pool, index, q, k_cur, v_cur, out) in layers:
+            B.pf_build_index(pool, index, Lq)
+            if events is not None:
+                e0, e1 = ev(), ev()
+                e0.record()
+            B.pf_ragged_attn_fwd(pool, index, q, k_cur, v_cur, out, workspace)
+            if events is not None:
+                e1.record()
+                events.append((e0, e1))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # effective work from the index the library built (history frames selected per head)
+    flops = 0.0
+    kv_bytes = 0.0
+    for (pool, index, *_rest) in layers:
+        for n in index.sel_count.cpu().tolist():
+            lkv = n * tpf + Lq
+            flops += 4.0 * Lq * lkv * D
+            kv_bytes += 2.0 * lkv * D * 2
+
+    events = []
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    ms_per_step = wall * 1e3 / args.steps
+    attn_ms = [a.elapsed_time(b) for a, b in events]
+    attn_ms_avg = float(np.mean(attn_ms))
+    flops_per_launch = flops / n_layers
+    achieved = flops_per_launch / (attn_ms_avg * 1e-3) / 1e12
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    result = {
+        "metric": "ragged-attn effective TFLOP/s (retained keys)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %d layers x %d heads, head_dim %d, %d tokens/frame, %d-token query chunk, "
+                               "%d history frames" % (w.name, n_layers, H, D, tpf, Lq, T),
+                   "step": "per layer pf_build_index + pf_ragged_attn_fwd, %d layers back to back on one stream" % n_layers,
+                   "effective_tflop_per_step": round(flops / 1e12, 3),
+                   "attn_variant": int(layers[0][1].c.variant),
+                   "seg_tiles": int(os.environ.get("PF_SEG_TILES", "0")) or "default"},
+        "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "roofline": {"kernel": "pf_attn_kernel", "bound": "mfma", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None, "avg_launch_ms": round(attn_ms_avg, 4),
+                     "flop_per_launch": flops_per_launch, "launches_timed": len(attn_ms)},
+        "pool_append": {"kernel": "pf_pool_append_kernel", "bound": "hbm",
+                        "what": "the append of %d frames that brings each layer's pool to %d frames "
+                                "(new frames + left-packed survivors, K and V, read + write)" % (w.chunk_frames, T),
+                        "avg_launch_ms": round(float(np.mean(append_ms)), 4),
+                        "achieved": round(float(np.sum(append_bytes)) / (float(np.sum(append_ms)) * 1e-3) / 1e9, 1),
+                        "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": round(float(np.sum(append_bytes)) / (float(np.sum(append_ms)) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+    }
+
+    # ---------------------------------------------------------------- cpu_baseline: the oracle on a bounded sample
+    if not args.no_cpu:
+        from oracle import attention as OA
+        from oracle.pool import PoolOracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        import gpu_common as G
+        pols, keep_k, keep_v, keep_s = hist0
+        pool_o = PoolOracle(pols, tpf, D)
+        for k_new, v_new, sc in zip(keep_k, keep_v, keep_s):
+            pool_o.append(synth.bits(k_new), synth.bits(v_new), sc.numpy())
+        sel_count, sel_frames, _, _ = pool_o.build_index(layers[0][1].max_sel)
+        rows = G.sample_rows(Lq, args.cpu_rows, 12345)
+        pool, index, q, k_cur, v_cur, out = layers[0]
+        qc, kc, vc = q.cpu(), k_cur.cpu(), v_cur.cpu()
+        OA.num_threads()
+        t0 = time.perf_counter()
+        want = G.oracle_attention(pool_o, sel_count, sel_frames, qc, kc, vc, rows=rows)
+        cpu_s = time.perf_counter() - t0
+        cpu_flops = sum(4.0 * len(rows) * (int(n) * tpf + Lq) * D for n in sel_count)
+        worst_abs, worst_rel = G.compare_attention(out, want, rows=rows, label="bench layer 0")
+        result["cpu_baseline"] = {"value": round(cpu_flops / cpu_s / 1e12, 6), "unit": "TFLOP/s",
+                                  "cores": OA.num_threads(), "kind": "oracle",
+                                  "sample": "layer 0, all %d heads, %d seeded query rows per head (%.1f GFLOP effective, "
+                                            "%.1f s incl. assembling each head's keys)" % (H, len(rows), cpu_flops / 1e9, cpu_s),
+                                  "parity_max_abs": float(worst_abs), "parity_rel_l2": float(worst_rel)}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
