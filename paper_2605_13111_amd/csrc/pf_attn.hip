@@ -18,6 +18,7 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // 16-byte register quad
 
 constexpr int ATT_THREADS = 256;
 constexpr int ATT_WAVES = 4;
@@ -47,6 +48,65 @@ __device__ __forceinline__ float partner_sum(float x) {
   return __int_as_float(r[0]) + __int_as_float(r[1]);
 }
 
+// Global -> register load of one 64-key tile of a head's ragged key sequence
+// [selected frames || chunk].  (j0, r0) locate the tile's first key: frame index and offset in it, j0 = n_sel
+// meaning the chunk.  Common case (tile inside one frame, no ragged tail): one wave-uniform base pointer plus
+// a per-thread constant offset.  Otherwise each row is located on its own.
+template <int D, int NP, int RPP>
+__device__ __forceinline__ void attn_load_tile(u32x4 (&kreg)[NP], u32x4 (&vreg)[NP], int kt, int j0, int r0, int n_sel,
+                                               int tpf, int lkv, int hist_tokens, int lrow, int lchunk,
+                                               unsigned thread_off, const __bf16 *k_pool, const __bf16 *v_pool,
+                                               const __bf16 *kcur, const __bf16 *vcur, const int32_t *slots_h) {
+  constexpr unsigned PASS_BYTES = RPP * D * 2;
+  const int last = lkv - 1 - kt * PF_BK;                     // last valid row of this tile
+  const bool in_hist = j0 < n_sel;
+  const bool simple = last >= PF_BK - 1 && (!in_hist || r0 + PF_BK <= tpf);
+  if (simple) {
+    const char *kb, *vb;
+    if (in_hist) {
+      const size_t e = ((size_t)slots_h[j0] * tpf + r0) * D;
+      kb = (const char *)(k_pool + e);
+      vb = (const char *)(v_pool + e);
+    } else {
+      kb = (const char *)(kcur + (size_t)r0 * D);
+      vb = (const char *)(vcur + (size_t)r0 * D);
+    }
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      kreg[p] = *(const u32x4 *)(kb + (thread_off + p * PASS_BYTES));
+      vreg[p] = *(const u32x4 *)(vb + (thread_off + p * PASS_BYTES));
+    }
+  } else {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const int t = kt * PF_BK + pf_min(lrow + p * RPP, last);    // rows past the end re-read the last key
+      size_t e;
+      const __bf16 *kb = k_pool, *vb = v_pool;
+      if (t >= hist_tokens) {
+        e = (size_t)(t - hist_tokens) * D;
+        kb = kcur;
+        vb = vcur;
+      } else {
+        const int j = t / tpf;
+        e = ((size_t)slots_h[j] * tpf + (t - j * tpf)) * D;
+      }
+      kreg[p] = *(const u32x4 *)(kb + e + lchunk * 8);
+      vreg[p] = *(const u32x4 *)(vb + e + lchunk * 8);
+    }
+  }
+}
+
+template <int NP, int RPP, int KS, int VS>
+__device__ __forceinline__ void attn_store_tile(const u32x4 (&kreg)[NP], const u32x4 (&vreg)[NP], __bf16 *sK, __bf16 *sV,
+                                                int lrow, int lchunk) {
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    const int row = lrow + p * RPP;
+    *(u32x4 *)(&sK[row * KS + lchunk * 8]) = kreg[p];
+    *(u32x4 *)(&sV[row * VS + lchunk * 8]) = vreg[p];
+  }
+}
+
 template <int D, int NQB>
 __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kernel(AttnParams P) {
   constexpr int BQ = ATT_WAVES * 32 * NQB;
@@ -63,7 +123,6 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
 
   __shared__ __attribute__((aligned(16))) __bf16 sK[2][BK * KS];
   __shared__ __attribute__((aligned(16))) __bf16 sV[2][BK * VS];
-  __shared__ int32_t sSlot[PF_MAX_SEL];
   __shared__ int32_t sFlag;
 
   const PfWorkItem it = P.items[blockIdx.x];
@@ -77,8 +136,6 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
   const int lkv = hist_tokens + P.q_tokens;
   const int tpf = P.tpf;
 
-  for (int j = tid; j < n_sel; j += ATT_THREADS) sSlot[j] = P.sel_slots[(size_t)h * P.max_sel + j];
-
   // ---- Q^T fragments: lane (l32, g) holds, for its query row, d = 16*ks + 8*g .. +7 ----
   bf16x8 qf[NQB][NKS];
   const __bf16 *qh = P.q + (size_t)h * P.q_tokens * D;
@@ -90,52 +147,20 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
   }
 
   // ---- K/V tile loader: thread (lrow, lchunk) copies one 16-byte chunk of NP rows per tile ----
+  // j0 / r0 (wave-uniform) = frame index (n_sel = the chunk) and offset in it of the tile's first key.
   const int lrow = tid / CPR, lchunk = tid % CPR;
   const __bf16 *kcur = P.k_cur + (size_t)h * P.q_tokens * D;
   const __bf16 *vcur = P.v_cur + (size_t)h * P.q_tokens * D;
-  uint4 kreg[NP], vreg[NP];
-  // position of the first key of the current tile: frame index j0 (n_sel = the chunk) and offset r0
+  const int32_t *slots_h = P.sel_slots + (size_t)h * P.max_sel;
+  u32x4 kreg[NP], vreg[NP];
   int j0, r0;
   {
     const int t0 = it.kt0 * BK;
     if (t0 >= hist_tokens) { j0 = n_sel; r0 = t0 - hist_tokens; }
     else { j0 = t0 / tpf; r0 = t0 - j0 * tpf; }
   }
-  __syncthreads();   // sSlot ready
-
-  auto load_tile = [&](int kt) {
-    const int last = lkv - 1 - kt * BK;                      // last valid row of this tile
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      int r = r0 + pf_min(lrow + p * RPP, last);
-      int j = j0;
-      while (j < n_sel && r >= tpf) { r -= tpf; ++j; }
-      size_t off;
-      const __bf16 *kb, *vb;
-      if (j < n_sel) {
-        off = ((size_t)sSlot[j] * tpf + r) * D + lchunk * 8;
-        kb = P.k_pool; vb = P.v_pool;
-      } else {
-        off = (size_t)r * D + lchunk * 8;
-        kb = kcur; vb = vcur;
-      }
-      kreg[p] = *(const uint4 *)(kb + off);
-      vreg[p] = *(const uint4 *)(vb + off);
-    }
-  };
-  auto advance_tile = [&]() {
-    r0 += BK;
-    while (j0 < n_sel && r0 >= tpf) { r0 -= tpf; ++j0; }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      const int row = lrow + p * RPP;
-      *(uint4 *)(&sK[buf][row * KS + lchunk * 8]) = kreg[p];
-      *(uint4 *)(&sV[buf][row * VS + lchunk * 8]) = vreg[p];
-    }
-  };
-
+  const unsigned thread_off = (unsigned)((lrow * D + lchunk * 8) * 2);      // bytes, row lrow of a tile
+  constexpr unsigned PASS_BYTES = RPP * D * 2;
   // ---- accumulators ----
   f32x16 o[NQB][NDB];
   float m_run[NQB], l_run[NQB];
@@ -153,14 +178,24 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
   const int v_lane = (4 * g + ((lane & 15) >> 2)) * VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
   const float c = P.scale_log2;
 
-  load_tile(it.kt0);
-  store_tile(0);
+  attn_load_tile<D, NP, RPP>(kreg, vreg, it.kt0, j0, r0, n_sel, tpf, lkv, hist_tokens, lrow, lchunk, thread_off,
+                              P.k_pool, P.v_pool, kcur, vcur, slots_h);
+  attn_store_tile<NP, RPP, KS, VS>(kreg, vreg, sK[0], sV[0], lrow, lchunk);
   __syncthreads();
 
   int buf = 0;
   for (int kt = it.kt0; kt < it.kt1; ++kt) {
     const bool more = kt + 1 < it.kt1;
-    if (more) { advance_tile(); load_tile(kt + 1); }
+    if (more) {
+      r0 += BK;                                            // position of the next tile's first key
+      if (j0 < n_sel) {
+        if (tpf >= BK) { if (r0 >= tpf) { r0 -= tpf; ++j0; } }
+        else { const int adv = r0 / tpf; r0 -= adv * tpf; j0 += adv; }
+        if (j0 > n_sel) { r0 += (j0 - n_sel) * tpf; j0 = n_sel; }
+      }
+      attn_load_tile<D, NP, RPP>(kreg, vreg, kt + 1, j0, r0, n_sel, tpf, lkv, hist_tokens, lrow, lchunk, thread_off,
+                                  P.k_pool, P.v_pool, kcur, vcur, slots_h);
+    }
 
     // ---- S^T = K Q^T ----
     f32x16 s[NQB][NKB];
@@ -239,7 +274,7 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
       }
     }
 
-    if (more) store_tile(buf ^ 1);
+    if (more) attn_store_tile<NP, RPP, KS, VS>(kreg, vreg, sK[buf ^ 1], sV[buf ^ 1], lrow, lchunk);
     __syncthreads();
     buf ^= 1;
   }
