@@ -48,6 +48,25 @@ __device__ __forceinline__ float partner_sum(float x) {
   return __int_as_float(r[0]) + __int_as_float(r[1]);
 }
 
+// Partial results cross workgroups that may run on different dies, each with its own L2.  They are written
+// and read with device-scope (relaxed atomic) 64-bit accesses, which go through to the memory side that all
+// dies share; no L2 write-back fence is needed, only the wait for the stores' completion before the arrival
+// counter is bumped.
+__device__ __forceinline__ void st_dev2(float *p, float a, float b) {
+  const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+  __hip_atomic_store((unsigned long long *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_dev2(const float *p) {
+  const unsigned long long v = __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((unsigned)v), __uint_as_float((unsigned)(v >> 32)));
+}
+__device__ __forceinline__ void st_dev1(float *p, float a) {
+  __hip_atomic_store(p, a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev1(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Global -> register load of one 64-key tile of a head's ragged key sequence
 // [selected frames || chunk].  (j0, r0) locate the tile's first key: frame index and offset in it, j0 = n_sel
 // meaning the chunk.  Common case (tile inside one frame, no ragged tail): one wave-uniform base pointer plus
@@ -315,13 +334,14 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
       for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          float4 w = make_float4(o[qb][db][i4 * 4], o[qb][db][i4 * 4 + 1], o[qb][db][i4 * 4 + 2], o[qb][db][i4 * 4 + 3]);
-          *(float4 *)(po + (size_t)lrow_q * D + db * 32 + 8 * i4 + 4 * g) = w;
+          float *dst = po + (size_t)lrow_q * D + db * 32 + 8 * i4 + 4 * g;
+          st_dev2(dst, o[qb][db][i4 * 4], o[qb][db][i4 * 4 + 1]);
+          st_dev2(dst + 2, o[qb][db][i4 * 4 + 2], o[qb][db][i4 * 4 + 3]);
         }
-      if (g == 0) { pm[lrow_q] = m_run[qb]; pl[lrow_q] = l_run[qb]; }
+      if (g == 0) { st_dev1(pm + lrow_q, m_run[qb]); st_dev1(pl + lrow_q, l_run[qb]); }
     }
   }
-  __threadfence();
+  __builtin_amdgcn_s_waitcnt(0);             // this wave's partial stores have completed
   __syncthreads();
   if (tid == 0) {
     const int arrived = atomicAdd(&P.counters[it.group], 1);
@@ -330,32 +350,64 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
   }
   __syncthreads();
   if (!sFlag) return;
-  __threadfence();
 
-  // merge: thread handles 4 consecutive d of one row at a time
-  __bf16 *oh = P.out + (size_t)h * P.q_tokens * D;
+  // ---- merge.  Phase A: per query row, the maximum M over the segments' running maxima and the total
+  // denominator L = sum_s 2^((m_s-M)c) l_s.  Phase B: out = sum_s 2^((m_s-M)c) O_s / L.  Both phases keep
+  // many independent loads in flight: the merge is pure memory latency otherwise. ----
+  float *sM = (float *)&sK[0][0];            // the K/V tiles are dead: every wave passed the loop's last barrier
+  float *sInvL = sM + BQ;
   const float *base = P.workspace + (size_t)it.part0 * part_floats;
   const size_t seg_stride = (size_t)P.n_qt * part_floats;
-  for (int e = tid; e < BQ * (D / 4); e += ATT_THREADS) {
-    const int r = e / (D / 4), dc = (e % (D / 4)) * 4;
-    const int row = it.q0 + r;
-    if (row >= P.q_tokens) continue;
+  const int nseg = it.nseg;
+  for (int r = tid; r < BQ; r += ATT_THREADS) {
+    const float *pm = base + (size_t)BQ * D + r;
     float mmax = -3.0e38f;
-    for (int sgi = 0; sgi < it.nseg; ++sgi) mmax = fmaxf(mmax, base[sgi * seg_stride + (size_t)BQ * D + r]);
+#pragma unroll 8
+    for (int sgi = 0; sgi < nseg; ++sgi) mmax = fmaxf(mmax, ld_dev1(pm + sgi * seg_stride));
     float lsum = 0.0f;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int sgi = 0; sgi < it.nseg; ++sgi) {
-      const float *ps = base + sgi * seg_stride;
-      const float w = fast_exp2((ps[(size_t)BQ * D + r] - mmax) * c);
-      lsum += w * ps[(size_t)BQ * D + BQ + r];
-      const float4 v = *(const float4 *)(ps + (size_t)r * D + dc);
-      acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
+#pragma unroll 8
+    for (int sgi = 0; sgi < nseg; ++sgi)
+      lsum += fast_exp2((ld_dev1(pm + sgi * seg_stride) - mmax) * c) * ld_dev1(pm + sgi * seg_stride + BQ);
+    sM[r] = mmax;
+    sInvL[r] = 1.0f / lsum;
+  }
+  __syncthreads();
+  __bf16 *oh = P.out + (size_t)h * P.q_tokens * D;
+  constexpr int EG = 4;                                        // output quads per thread in flight
+  static_assert((BQ * (D / 4)) % (ATT_THREADS * EG) == 0, "merge tiling");
+  for (int e0 = tid; e0 < BQ * (D / 4); e0 += ATT_THREADS * EG) {
+    int r[EG], dc[EG];
+    float mrow[EG];
+    float4 acc[EG];
+#pragma unroll
+    for (int k = 0; k < EG; ++k) {
+      const int e = e0 + k * ATT_THREADS;
+      r[k] = e / (D / 4);
+      dc[k] = (e % (D / 4)) * 4;
+      mrow[k] = sM[r[k]];
+      acc[k] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    const float inv = 1.0f / lsum;
-    bf16x4 w4;
-    w4[0] = (__bf16)(acc.x * inv); w4[1] = (__bf16)(acc.y * inv);
-    w4[2] = (__bf16)(acc.z * inv); w4[3] = (__bf16)(acc.w * inv);
-    *(bf16x4 *)(oh + (size_t)row * D + dc) = w4;
+#pragma unroll 4
+    for (int sgi = 0; sgi < nseg; ++sgi) {
+      const float *ps = base + sgi * seg_stride;
+#pragma unroll
+      for (int k = 0; k < EG; ++k) {
+        const float w = fast_exp2((ld_dev1(ps + (size_t)BQ * D + r[k]) - mrow[k]) * c);
+        const float2 va = ld_dev2(ps + (size_t)r[k] * D + dc[k]);
+        const float2 vb = ld_dev2(ps + (size_t)r[k] * D + dc[k] + 2);
+        acc[k].x += w * va.x; acc[k].y += w * va.y; acc[k].z += w * vb.x; acc[k].w += w * vb.y;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < EG; ++k) {
+      const int row = it.q0 + r[k];
+      if (row >= P.q_tokens) continue;
+      const float inv = sInvL[r[k]];
+      bf16x4 w4;
+      w4[0] = (__bf16)(acc[k].x * inv); w4[1] = (__bf16)(acc[k].y * inv);
+      w4[2] = (__bf16)(acc[k].z * inv); w4[3] = (__bf16)(acc[k].w * inv);
+      *(bf16x4 *)(oh + (size_t)row * D + dc[k]) = w4;
+    }
   }
 }
 
