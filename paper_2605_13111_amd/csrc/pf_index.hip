@@ -3,6 +3,7 @@
 #include "pf_internal.h"
 
 constexpr int INDEX_THREADS = 256;
+constexpr int INDEX_STAGE_SLOTS = 4096;     // pool slots whose tables are staged in LDS
 
 struct IndexParams {
   const pf_head_policy *policy;
@@ -12,6 +13,7 @@ struct IndexParams {
   PfWorkHeader *header;
   int32_t *counters, *scratch;
   PfWorkItem *items;
+  long long total_slots;
   int n_heads, T, tpf, max_sel, q_tokens, n_qt, bq, seg_tiles, variant;
   int host_teams, host_blocks, host_partials;
 };
@@ -49,10 +51,30 @@ __global__ __launch_bounds__(INDEX_THREADS) void pf_build_index_kernel(IndexPara
   __shared__ int32_t s_nkvt[PF_MAX_HEADS];
   __shared__ int32_t s_team0[PF_MAX_HEADS];     // first team rank of the head (teams sorted by length)
   __shared__ int32_t s_part0[PF_MAX_HEADS];     // first partial slot of the head, -1 if unsplit
+  __shared__ int32_t s_selcount[PF_MAX_HEADS];
+  __shared__ int32_t s_ids[INDEX_STAGE_SLOTS];
+  __shared__ float s_scores[INDEX_STAGE_SLOTS];
   __shared__ int32_t s_error;
   const int tid = threadIdx.x;
   if (tid == 0) s_error = 0;
   __syncthreads();
+
+  // ---- stage the pool tables in LDS (one coalesced pass) so the per-head walks below do not pay a
+  // global-memory round trip per frame; pools with more slots than fit are read in place ----
+  const bool staged = P.total_slots <= INDEX_STAGE_SLOTS;
+  if (staged) {
+    for (int i = tid; i < (int)P.total_slots; i += INDEX_THREADS) {
+      s_ids[i] = P.frame_ids[i];
+      s_scores[i] = P.frame_score[i];
+    }
+  }
+  for (int i = tid; i < P.n_heads * P.max_sel; i += INDEX_THREADS) {     // unused entries read -1
+    P.sel_frames[i] = -1;
+    P.sel_slots[i] = -1;
+  }
+  __syncthreads();
+  const int32_t *ids = staged ? s_ids : P.frame_ids;
+  const float *scores = staged ? s_scores : P.frame_score;
 
   // ---- selection: one thread per head walks the head's resident frames (ascending ids) ----
   for (int h = tid; h < P.n_heads; h += INDEX_THREADS) {
@@ -64,14 +86,14 @@ __global__ __launch_bounds__(INDEX_THREADS) void pf_build_index_kernel(IndexPara
                            pf_middle_count(P.T, pol.sink, pol.recent) > pol.cap;
     int n = 0;
     for (int j = 0; j < n_res; ++j) {
-      const int f = P.frame_ids[base + j];
+      const int f = ids[base + j];
       int rank = 0;
       if (need_rank && f >= mid_lo && f < mid_hi) {
-        const float sc = P.frame_score[base + j];
+        const float sc = scores[base + j];
         for (int g = 0; g < n_res; ++g) {
-          const int fg = P.frame_ids[base + g];
+          const int fg = ids[base + g];
           if (fg < mid_lo || fg >= mid_hi) continue;
-          const float sg = P.frame_score[base + g];
+          const float sg = scores[base + g];
           rank += (sg > sc || (sg == sc && fg < f)) ? 1 : 0;
         }
       }
@@ -82,11 +104,8 @@ __global__ __launch_bounds__(INDEX_THREADS) void pf_build_index_kernel(IndexPara
       }
       ++n;
     }
-    for (int j = n; j < P.max_sel; ++j) {
-      P.sel_frames[(size_t)h * P.max_sel + j] = -1;
-      P.sel_slots[(size_t)h * P.max_sel + j] = -1;
-    }
     P.sel_count[h] = n;
+    s_selcount[h] = n;
     // The host sized the launch from the closed-form count; a mismatch means the pool does not hold
     // what the policy asks for (it was not filled through pf_cache_append).
     if (n != pf_sel_count_impl(pol, P.T) || n > P.max_sel) atomicExch(&s_error, 1);
@@ -102,7 +121,7 @@ __global__ __launch_bounds__(INDEX_THREADS) void pf_build_index_kernel(IndexPara
     int cu = 0, parts = 0;
     P.cu_seqlens[0] = 0;
     for (int h = 0; h < P.n_heads; ++h) {
-      cu += P.sel_count[h] * P.tpf;
+      cu += s_selcount[h] * P.tpf;
       P.cu_seqlens[h + 1] = cu;
       s_part0[h] = s_nseg[h] > 1 ? parts : -1;
       if (s_nseg[h] > 1) parts += s_nseg[h] * P.n_qt;
@@ -196,6 +215,7 @@ extern "C" int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens
   P.counters = (int32_t *)(w + L.counters_off);
   P.scratch = (int32_t *)(w + L.scratch_off);
   P.items = (PfWorkItem *)(w + L.items_off);
+  P.total_slots = pool->total_slots;
   P.n_heads = pool->n_heads;
   P.T = pool->T_host;
   P.tpf = pool->tokens_per_frame;
