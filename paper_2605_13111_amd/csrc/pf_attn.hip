@@ -1,8 +1,14 @@
 // Ragged-cache attention forward (Sec. 4.3; Eq. 1 per head over [selected frames || chunk]).
 //
-// One launch per layer.  A workgroup (4 waves) owns BQ = 128*NQB query rows of one head and a run of
-// 64-key tiles of that head's ragged key sequence; heads with many keys are cut into several runs
-// whose partial results are merged by the last workgroup to finish (no spinning).
+// One launch per layer.  A workgroup (4 waves) owns BQ query rows of one head and a run of 64-key tiles of
+// that head's ragged key sequence; heads with many keys are cut into several runs whose partial results
+// are merged by the last workgroup to finish (no spinning).  Two kernels share the layouts below:
+//   pf_attn_kernel       BQ = 128, 32 query rows per wave, two workgroups per CU (the second wave on each
+//                        SIMD hides the first one's softmax)
+//   pf_attn_pipe_kernel  BQ = 256, 64 query rows per wave (every K / V fragment read from LDS feeds two
+//                        MFMAs, halving LDS traffic), one wave per SIMD; S^T of the NEXT 32 keys is computed
+//                        while the softmax of the current 32 runs, so matrix and vector work overlap inside
+//                        one instruction stream
 //
 // Per tile, on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate):
 //   S^T = K . Q^T     A operand = K rows from LDS, B operand = Q^T held in registers
@@ -15,6 +21,7 @@
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -22,6 +29,11 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // 16-byte reg
 
 constexpr int ATT_THREADS = 256;
 constexpr int ATT_WAVES = 4;
+// Exponent headroom (log2 units) a score may have over the reference maximum before the accumulators
+// must be rescaled: weights stay below 2^8 in the rescaling loop, 2^60 in the pipelined loop (fp32 and
+// bf16 share the 8-bit exponent, so both hold such weights without loss of relative precision).
+constexpr float ATT_LAZY_LOG2 = 8.0f;
+constexpr float ATT_PIPE_LOG2 = 60.0f;
 
 struct AttnParams {
   const __bf16 *q, *k_cur, *v_cur, *k_pool, *v_pool;
@@ -49,8 +61,8 @@ __device__ __forceinline__ float partner_sum(float x) {
 }
 
 // Partial results cross workgroups that may run on different dies, each with its own L2.  They are written
-// and read with device-scope (relaxed atomic) 64-bit accesses, which go through to the memory side that all
-// dies share; no L2 write-back fence is needed, only the wait for the stores' completion before the arrival
+// and read with device-scope (relaxed atomic) accesses, which go through to the memory side that all dies
+// share; no L2 write-back fence is needed, only the wait for the stores' completion before the arrival
 // counter is bumped.
 __device__ __forceinline__ void st_dev2(float *p, float a, float b) {
   const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
@@ -67,153 +79,193 @@ __device__ __forceinline__ float ld_dev1(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Global -> register load of one 64-key tile of a head's ragged key sequence
-// [selected frames || chunk].  (j0, r0) locate the tile's first key: frame index and offset in it, j0 = n_sel
-// meaning the chunk.  Common case (tile inside one frame, no ragged tail): one wave-uniform base pointer plus
-// a per-thread constant offset.  Otherwise each row is located on its own.
+// ---------------------------------------------------------------------------------------------------
+// Tile addressing.  A head's key sequence is [selected frame 0 | selected frame 1 | ... | chunk]; frames
+// sit anywhere in the pool (slot table), the chunk in k_cur / v_cur.  Tiles of 64 keys ignore frame borders.
+// ---------------------------------------------------------------------------------------------------
+struct TilePos {   // where a tile's first key lives: frame index (n_sel = the chunk) and offset in it
+  int j, r;
+};
+__device__ __forceinline__ TilePos tile_pos_init(int kt, int hist_tokens, int n_sel, int tpf) {
+  TilePos p;
+  const int t0 = kt * PF_BK;
+  if (t0 >= hist_tokens) { p.j = n_sel; p.r = t0 - hist_tokens; }
+  else { p.j = t0 / tpf; p.r = t0 - p.j * tpf; }
+  return p;
+}
+__device__ __forceinline__ void tile_pos_advance(TilePos &p, int n_sel, int tpf) {
+  p.r += PF_BK;
+  if (p.j < n_sel) {
+    if (tpf >= PF_BK) { if (p.r >= tpf) { p.r -= tpf; ++p.j; } }
+    else { const int adv = p.r / tpf; p.r -= adv * tpf; p.j += adv; }
+    if (p.j > n_sel) { p.r += (p.j - n_sel) * tpf; p.j = n_sel; }
+  }
+}
+
+struct HeadKV {     // everything a loader thread needs to find keys of one head
+  const __bf16 *k_pool, *v_pool, *k_cur, *v_cur;
+  const int32_t *slots;
+  int n_sel, tpf, hist_tokens, lkv;
+  int lrow, lchunk;
+  unsigned thread_off;
+};
+
+// Global -> register load of one 64-key tile of one tensor.  Common case (tile inside one frame, no ragged
+// tail): one wave-uniform base pointer plus a per-thread constant offset.  Otherwise every row is located
+// on its own (branch-free: both candidate addresses, then a select).
 template <int D, int NP, int RPP>
-__device__ __forceinline__ void attn_load_tile(u32x4 (&kreg)[NP], u32x4 (&vreg)[NP], int kt, int j0, int r0, int n_sel,
-                                               int tpf, int lkv, int hist_tokens, int lrow, int lchunk,
-                                               unsigned thread_off, const __bf16 *k_pool, const __bf16 *v_pool,
-                                               const __bf16 *kcur, const __bf16 *vcur, const int32_t *slots_h) {
+__device__ __forceinline__ void attn_load_rows(u32x4 (&reg)[NP], int kt, TilePos pos, const HeadKV &H, const __bf16 *pool,
+                                               const __bf16 *cur) {
   constexpr unsigned PASS_BYTES = RPP * D * 2;
-  const int last = lkv - 1 - kt * PF_BK;                     // last valid row of this tile
-  const bool in_hist = j0 < n_sel;
-  const bool simple = last >= PF_BK - 1 && (!in_hist || r0 + PF_BK <= tpf);
+  const int last = H.lkv - 1 - kt * PF_BK;
+  const bool in_hist = pos.j < H.n_sel;
+  const bool simple = last >= PF_BK - 1 && (!in_hist || pos.r + PF_BK <= H.tpf);
   if (simple) {
-    const char *kb, *vb;
-    if (in_hist) {
-      const size_t e = ((size_t)slots_h[j0] * tpf + r0) * D;
-      kb = (const char *)(k_pool + e);
-      vb = (const char *)(v_pool + e);
-    } else {
-      kb = (const char *)(kcur + (size_t)r0 * D);
-      vb = (const char *)(vcur + (size_t)r0 * D);
-    }
+    const char *b = in_hist ? (const char *)(pool + ((size_t)H.slots[pos.j] * H.tpf + pos.r) * D)
+                            : (const char *)(cur + (size_t)pos.r * D);
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      kreg[p] = *(const u32x4 *)(kb + (thread_off + p * PASS_BYTES));
-      vreg[p] = *(const u32x4 *)(vb + (thread_off + p * PASS_BYTES));
-    }
+    for (int p = 0; p < NP; ++p) reg[p] = *(const u32x4 *)(b + (H.thread_off + p * PASS_BYTES));
   } else {
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-      const int t = kt * PF_BK + pf_min(lrow + p * RPP, last);    // rows past the end re-read the last key
-      size_t e;
-      const __bf16 *kb = k_pool, *vb = v_pool;
-      if (t >= hist_tokens) {
-        e = (size_t)(t - hist_tokens) * D;
-        kb = kcur;
-        vb = vcur;
-      } else {
-        const int j = t / tpf;
-        e = ((size_t)slots_h[j] * tpf + (t - j * tpf)) * D;
-      }
-      kreg[p] = *(const u32x4 *)(kb + e + lchunk * 8);
-      vreg[p] = *(const u32x4 *)(vb + e + lchunk * 8);
+      const int t = kt * PF_BK + pf_min(H.lrow + p * RPP, last);    // rows past the end re-read the last key
+      const bool in_chunk = t >= H.hist_tokens;
+      const int th = in_chunk ? 0 : t;
+      const int j = th / H.tpf;
+      const size_t e_hist = ((size_t)pf_max(H.slots[j], 0) * H.tpf + (th - j * H.tpf)) * D;
+      const size_t e = in_chunk ? (size_t)(t - H.hist_tokens) * D : e_hist;
+      const __bf16 *b = in_chunk ? cur : pool;
+      reg[p] = *(const u32x4 *)(b + e + H.lchunk * 8);
     }
   }
 }
 
-template <int NP, int RPP, int KS, int VS>
-__device__ __forceinline__ void attn_store_tile(const u32x4 (&kreg)[NP], const u32x4 (&vreg)[NP], __bf16 *sK, __bf16 *sV,
-                                                int lrow, int lchunk) {
+template <int NP, int RPP, int STRIDE>
+__device__ __forceinline__ void attn_store_rows(const u32x4 (&reg)[NP], __bf16 *dst, int lrow, int lchunk) {
 #pragma unroll
-  for (int p = 0; p < NP; ++p) {
-    const int row = lrow + p * RPP;
-    *(u32x4 *)(&sK[row * KS + lchunk * 8]) = kreg[p];
-    *(u32x4 *)(&sV[row * VS + lchunk * 8]) = vreg[p];
+  for (int p = 0; p < NP; ++p) *(u32x4 *)(&dst[(lrow + p * RPP) * STRIDE + lchunk * 8]) = reg[p];
+}
+
+// Global -> LDS copy of one 64-key tile of one tensor WITHOUT passing through registers (head_dim 128 only):
+// each wave moves 16 rows, one 256-byte row per instruction (lane i carries 4 bytes to row start + 4*i), so
+// rows keep their padded LDS stride.  The data lands asynchronously; the barrier that ends the iteration
+// (preceded by the wait for outstanding vector-memory operations) publishes it.
+template <int D, int STRIDE>
+__device__ __forceinline__ void dma_tile(int kt, TilePos pos, const HeadKV &H, const __bf16 *pool, const __bf16 *cur,
+                                         __bf16 *sdst, int wave, int lane) {
+  static_assert(D == 128, "one row = 64 lanes x 4 bytes");
+  constexpr int ROWS = PF_BK / ATT_WAVES;
+  typedef const __attribute__((address_space(1))) void *gptr_t;
+  typedef __attribute__((address_space(3))) void *lptr_t;
+  const int last = H.lkv - 1 - kt * PF_BK;
+  const bool in_hist = pos.j < H.n_sel;
+  const bool simple = last >= PF_BK - 1 && (!in_hist || pos.r + PF_BK <= H.tpf);
+  if (simple) {
+    const __bf16 *b = in_hist ? pool + ((size_t)H.slots[pos.j] * H.tpf + pos.r) * D : cur + (size_t)pos.r * D;
+    b += (size_t)(wave * ROWS) * D + lane * 2;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+      __builtin_amdgcn_global_load_lds((gptr_t)(b + r * D), (lptr_t)(sdst + (wave * ROWS + r) * STRIDE), 4, 0, 0);
+  } else {
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+      const int row = wave * ROWS + r;
+      const int t = kt * PF_BK + pf_min(row, last);               // rows past the end re-read the last key
+      const bool in_chunk = t >= H.hist_tokens;
+      const int th = in_chunk ? 0 : t;
+      const int j = th / H.tpf;
+      const size_t e_hist = ((size_t)pf_max(H.slots[j], 0) * H.tpf + (th - j * H.tpf)) * D;
+      const size_t e = in_chunk ? (size_t)(t - H.hist_tokens) * D : e_hist;
+      const __bf16 *b = (in_chunk ? cur : pool) + e + lane * 2;
+      __builtin_amdgcn_global_load_lds((gptr_t)b, (lptr_t)(sdst + row * STRIDE), 4, 0, 0);
+    }
   }
 }
 
+// V^T operand of O^T += V^T P^T for 16 keys x 32 channels: two LDS transpose reads whose row choice
+// (4g+r and 8+4g+r) reproduces the key order of the S^T accumulator registers.
+template <int VS>
+__device__ __forceinline__ bf16x8 read_vt(const __bf16 *vp) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(vp));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(vp + 8 * VS));
+  const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, av);
+}
+
+// The same V^T operands for one 16-key chunk (all D/32 channel blocks), read with hand-issued instructions.
+// The compiler treats the transpose-read builtin as a possible reader of every outstanding global -> LDS
+// copy and would wait for the copies of the NEXT tiles before each use; issued this way the reads only
+// wait for LDS (vt_wait), and the copies stay in flight for the whole tile.
+template <int NDB>
+struct VtFrags {
+  s16x4 lo[NDB], hi[NDB];
+};
+template <int VS, int NDB>
+__device__ __forceinline__ void vt_issue(VtFrags<NDB> &f, const __bf16 *vp) {
+  const unsigned addr = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) __bf16 *)vp;
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) {
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.lo[db]) : "v"(addr), "n"(db * 64));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi[db]) : "v"(addr), "n"(db * 64 + 8 * VS * 2));
+  }
+}
+// K operands of S^T = K Q^T for 32 keys (NKS k-steps of 16 channels), same hand-issued style.
+template <int NKS>
+struct KFrags {
+  u32x4 a[NKS];
+};
+template <int NKS>
+__device__ __forceinline__ void kf_issue(KFrags<NKS> &f, const __bf16 *kp) {
+  const unsigned addr = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) __bf16 *)kp;
+#pragma unroll
+  for (int k = 0; k < NKS; ++k) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.a[k]) : "v"(addr), "n"(k * 32));
+}
+__device__ __forceinline__ void kf_wait(KFrags<8> &f) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.a[4]), "+v"(f.a[5]), "+v"(f.a[6]), "+v"(f.a[7]));
+}
+__device__ __forceinline__ void vt_wait(VtFrags<4> &f, VtFrags<4> &h) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(f.lo[0]), "+v"(f.lo[1]), "+v"(f.lo[2]), "+v"(f.lo[3]), "+v"(f.hi[0]), "+v"(f.hi[1]), "+v"(f.hi[2]),
+                 "+v"(f.hi[3]), "+v"(h.lo[0]), "+v"(h.lo[1]), "+v"(h.lo[2]), "+v"(h.lo[3]), "+v"(h.hi[0]), "+v"(h.hi[1]),
+                 "+v"(h.hi[2]), "+v"(h.hi[3]));
+}
+
+// ---------------------------------------------------------------------------------------------------
+// The rescaling ("classic") loop over key tiles [kt0, kt1): load tile -> S^T -> online softmax with
+// running-maximum rescaling -> O^T.  Used by pf_attn_kernel and as the fallback of the pipelined kernel.
+// ---------------------------------------------------------------------------------------------------
 template <int D, int NQB>
-__global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kernel(AttnParams P) {
-  constexpr int BQ = ATT_WAVES * 32 * NQB;
+__device__ __forceinline__ void classic_loop(const HeadKV &H, int kt0, int kt1, const bf16x8 (&qf)[NQB][D / 16],
+                                             f32x16 (&o)[NQB][D / 32], float (&m_run)[NQB], float (&l_run)[NQB],
+                                             __bf16 (*sK)[PF_BK * (D + 8)], __bf16 (*sV)[PF_BK * (D + 32)], float c) {
   constexpr int BK = PF_BK;
   constexpr int KS = D + 8;            // K row stride in LDS (elements): +16 B so 32 rows spread over banks
   constexpr int VS = D + 32;           // V row stride: +64 B so the 4 rows of one transpose read do not collide
-  constexpr int CPR = D / 8;           // 16-byte chunks per row
-  constexpr int RPP = ATT_THREADS / CPR;   // rows loaded per pass
-  constexpr int NP = BK / RPP;         // passes per tile
-  constexpr int NKS = D / 16;          // k-steps of S^T = K Q^T
-  constexpr int NDB = D / 32;          // 32-row blocks of O^T
-  constexpr int NKB = BK / 32;         // 32-key blocks of S^T
-  constexpr int NS16 = BK / 16;        // k-steps of O^T += V^T P^T
-
-  __shared__ __attribute__((aligned(16))) __bf16 sK[2][BK * KS];
-  __shared__ __attribute__((aligned(16))) __bf16 sV[2][BK * VS];
-  __shared__ int32_t sFlag;
-
-  const PfWorkItem it = P.items[blockIdx.x];
-  if (it.head < 0) return;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  constexpr int CPR = D / 8, RPP = ATT_THREADS / CPR, NP = BK / RPP;
+  constexpr int NKS = D / 16, NDB = D / 32, NKB = BK / 32, NS16 = BK / 16;
+  const int lane = threadIdx.x & 63;
   const int l32 = lane & 31, g = lane >> 5;
-  const int h = it.head;
-  const int n_sel = P.sel_count[h];
-  const int hist_tokens = n_sel * P.tpf;
-  const int lkv = hist_tokens + P.q_tokens;
-  const int tpf = P.tpf;
-
-  // ---- Q^T fragments: lane (l32, g) holds, for its query row, d = 16*ks + 8*g .. +7 ----
-  bf16x8 qf[NQB][NKS];
-  const __bf16 *qh = P.q + (size_t)h * P.q_tokens * D;
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int row = pf_min(it.q0 + (wave * NQB + qb) * 32 + l32, P.q_tokens - 1);
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) qf[qb][ks] = *(const bf16x8 *)(qh + (size_t)row * D + ks * 16 + 8 * g);
-  }
-
-  // ---- K/V tile loader: thread (lrow, lchunk) copies one 16-byte chunk of NP rows per tile ----
-  // j0 / r0 (wave-uniform) = frame index (n_sel = the chunk) and offset in it of the tile's first key.
-  const int lrow = tid / CPR, lchunk = tid % CPR;
-  const __bf16 *kcur = P.k_cur + (size_t)h * P.q_tokens * D;
-  const __bf16 *vcur = P.v_cur + (size_t)h * P.q_tokens * D;
-  const int32_t *slots_h = P.sel_slots + (size_t)h * P.max_sel;
-  u32x4 kreg[NP], vreg[NP];
-  int j0, r0;
-  {
-    const int t0 = it.kt0 * BK;
-    if (t0 >= hist_tokens) { j0 = n_sel; r0 = t0 - hist_tokens; }
-    else { j0 = t0 / tpf; r0 = t0 - j0 * tpf; }
-  }
-  const unsigned thread_off = (unsigned)((lrow * D + lchunk * 8) * 2);      // bytes, row lrow of a tile
-  constexpr unsigned PASS_BYTES = RPP * D * 2;
-  // ---- accumulators ----
-  f32x16 o[NQB][NDB];
-  float m_run[NQB], l_run[NQB];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    m_run[qb] = -3.0e38f;
-    l_run[qb] = 0.0f;
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[qb][db][i] = 0.0f;
-  }
-
   const int k_lane = l32 * KS + 8 * g;                                           // K operand: row l32, d 8g..
   const int v_lane = (4 * g + ((lane & 15) >> 2)) * VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  const float c = P.scale_log2;
+  const float thr = ATT_LAZY_LOG2 / c;
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-  attn_load_tile<D, NP, RPP>(kreg, vreg, it.kt0, j0, r0, n_sel, tpf, lkv, hist_tokens, lrow, lchunk, thread_off,
-                              P.k_pool, P.v_pool, kcur, vcur, slots_h);
-  attn_store_tile<NP, RPP, KS, VS>(kreg, vreg, sK[0], sV[0], lrow, lchunk);
+  u32x4 kreg[NP], vreg[NP];
+  TilePos pos = tile_pos_init(kt0, H.hist_tokens, H.n_sel, H.tpf);
+  attn_load_rows<D, NP, RPP>(kreg, kt0, pos, H, H.k_pool, H.k_cur);
+  attn_load_rows<D, NP, RPP>(vreg, kt0, pos, H, H.v_pool, H.v_cur);
+  attn_store_rows<NP, RPP, KS>(kreg, sK[0], H.lrow, H.lchunk);
+  attn_store_rows<NP, RPP, VS>(vreg, sV[0], H.lrow, H.lchunk);
   __syncthreads();
 
   int buf = 0;
-  for (int kt = it.kt0; kt < it.kt1; ++kt) {
-    const bool more = kt + 1 < it.kt1;
+  for (int kt = kt0; kt < kt1; ++kt) {
+    const bool more = kt + 1 < kt1;
     if (more) {
-      r0 += BK;                                            // position of the next tile's first key
-      if (j0 < n_sel) {
-        if (tpf >= BK) { if (r0 >= tpf) { r0 -= tpf; ++j0; } }
-        else { const int adv = r0 / tpf; r0 -= adv * tpf; j0 += adv; }
-        if (j0 > n_sel) { r0 += (j0 - n_sel) * tpf; j0 = n_sel; }
-      }
-      attn_load_tile<D, NP, RPP>(kreg, vreg, kt + 1, j0, r0, n_sel, tpf, lkv, hist_tokens, lrow, lchunk, thread_off,
-                                  P.k_pool, P.v_pool, kcur, vcur, slots_h);
+      tile_pos_advance(pos, H.n_sel, H.tpf);
+      attn_load_rows<D, NP, RPP>(kreg, kt + 1, pos, H, H.k_pool, H.k_cur);
+      attn_load_rows<D, NP, RPP>(vreg, kt + 1, pos, H, H.v_pool, H.v_cur);
     }
 
     // ---- S^T = K Q^T ----
@@ -233,7 +285,7 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
       }
     }
     // ragged tail: keys at or beyond lkv exist only in the last tile of the head
-    const int valid = lkv - kt * BK;
+    const int valid = H.lkv - kt * BK;
     if (valid < BK) {
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb)
@@ -247,34 +299,49 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
         }
     }
 
-    // ---- online softmax (per lane: one query column) ----
+    // ---- online softmax (per lane: one query column).  The reference maximum m_run only moves when a row's
+    // tile maximum exceeds it by more than thr: exp2 arguments stay small and the accumulators are
+    // rescaled on a few early tiles only. ----
     bf16x8 pf[NQB][NS16];
+    float mx[NQB];
+    bool need = false;
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      float mx = s[qb][0][0];
+      float a = s[qb][0][0];
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[qb][kb][i]);
-      mx = partner_max(mx);
-      const float m_new = fmaxf(m_run[qb], mx);
-      const float alpha = fast_exp2((m_run[qb] - m_new) * c);
-      m_run[qb] = m_new;
-      const float mc = m_new * c;
-      float rs = 0.0f;
+        for (int i = 0; i < 16; ++i) a = fmaxf(a, s[qb][kb][i]);
+      mx[qb] = partner_max(a);
+      need = need || (mx[qb] > m_run[qb] + thr);
+    }
+    if (__builtin_amdgcn_ballot_w64(need) != 0) {
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        const float m_new = fmaxf(m_run[qb], mx[qb]);
+        const float alpha = fast_exp2((m_run[qb] - m_new) * c);
+        m_run[qb] = m_new;
+        l_run[qb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[qb][db][i] *= alpha;
+      }
+    }
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      const float mc = m_run[qb] * c;
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float p = fast_exp2(fmaf(s[qb][kb][i], c, -mc));
-          rs += p;
-          pf[qb][kb * 2 + (i >> 3)][i & 7] = (__bf16)p;
+        for (int i = 0; i < 16; i += 2) {
+          bf16x2 pk;
+          pk[0] = (__bf16)fast_exp2(fmaf(s[qb][kb][i], c, -mc));
+          pk[1] = (__bf16)fast_exp2(fmaf(s[qb][kb][i + 1], c, -mc));
+          l_run[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run[qb], false);   // sums the rounded weights
+          pf[qb][kb * 2 + (i >> 3)][i & 7] = pk[0];
+          pf[qb][kb * 2 + (i >> 3)][(i & 7) + 1] = pk[1];
         }
-      l_run[qb] = l_run[qb] * alpha + rs;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[qb][db][i] *= alpha;
     }
 
     // ---- O^T += V^T P^T ----
@@ -282,23 +349,37 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
     for (int s16 = 0; s16 < NS16; ++s16) {
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
-        const __bf16 *vp = &sV[buf][v_lane + s16 * 16 * VS + db * 32];
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(vp));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(vp + 8 * VS));
-        const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+        const bf16x8 a = read_vt<VS>(&sV[buf][v_lane + s16 * 16 * VS + db * 32]);
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb)
           o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[qb][s16], o[qb][db], 0, 0, 0);
       }
     }
 
-    if (more) attn_store_tile<NP, RPP, KS, VS>(kreg, vreg, sK[buf ^ 1], sV[buf ^ 1], lrow, lchunk);
+    if (more) {
+      attn_store_rows<NP, RPP, KS>(kreg, sK[buf ^ 1], H.lrow, H.lchunk);
+      attn_store_rows<NP, RPP, VS>(vreg, sV[buf ^ 1], H.lrow, H.lchunk);
+    }
     __syncthreads();
     buf ^= 1;
   }
+}
 
-  // ---- epilogue ----
+// ---------------------------------------------------------------------------------------------------
+// Final normalisation and store.  Unsplit heads write bf16 output directly; split heads park the
+// unnormalised partial (O, m, l) and the last segment to arrive merges all partials of its (head, query tile).
+// sScratch: at least 2*BQ floats of LDS that no wave reads any more (every wave passed the loop's last barrier).
+// ---------------------------------------------------------------------------------------------------
+template <int D, int NQB>
+__device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkItem &it, f32x16 (&o)[NQB][D / 32],
+                                              float (&m_run)[NQB], float (&l_run)[NQB], float *sScratch, int32_t *sFlagp) {
+  constexpr int BQ = ATT_WAVES * 32 * NQB;
+  constexpr int NDB = D / 32;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int h = it.head;
+  const float c = P.scale_log2;
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) l_run[qb] = partner_sum(l_run[qb]);
 
@@ -345,16 +426,16 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
   __syncthreads();
   if (tid == 0) {
     const int arrived = atomicAdd(&P.counters[it.group], 1);
-    sFlag = (arrived == it.nseg - 1) ? 1 : 0;
-    if (sFlag) P.counters[it.group] = 0;     // ready for the next launch on this index
+    *sFlagp = (arrived == it.nseg - 1) ? 1 : 0;
+    if (*sFlagp) P.counters[it.group] = 0;     // ready for the next launch on this index
   }
   __syncthreads();
-  if (!sFlag) return;
+  if (!*sFlagp) return;
 
-  // ---- merge.  Phase A: per query row, the maximum M over the segments' running maxima and the total
+  // ---- merge.  Phase A: per query row, the maximum M over the segments' reference maxima and the total
   // denominator L = sum_s 2^((m_s-M)c) l_s.  Phase B: out = sum_s 2^((m_s-M)c) O_s / L.  Both phases keep
   // many independent loads in flight: the merge is pure memory latency otherwise. ----
-  float *sM = (float *)&sK[0][0];            // the K/V tiles are dead: every wave passed the loop's last barrier
+  float *sM = sScratch;
   float *sInvL = sM + BQ;
   const float *base = P.workspace + (size_t)it.part0 * part_floats;
   const size_t seg_stride = (size_t)P.n_qt * part_floats;
@@ -411,9 +492,307 @@ __global__ __launch_bounds__(ATT_THREADS, (NQB == 1 ? 2 : 1)) void pf_attn_kerne
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Common set-up of a workgroup: its work item, the head's key layout, its Q^T fragments.
+// ---------------------------------------------------------------------------------------------------
 template <int D, int NQB>
-static int launch_attn(const AttnParams &P, int n_blocks, hipStream_t stream) {
-  hipLaunchKernelGGL((pf_attn_kernel<D, NQB>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
+__device__ __forceinline__ void attn_setup(const AttnParams &P, const PfWorkItem &it, HeadKV &H, bf16x8 (&qf)[NQB][D / 16]) {
+  constexpr int CPR = D / 8;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int h = it.head;
+  H.n_sel = P.sel_count[h];
+  H.tpf = P.tpf;
+  H.hist_tokens = H.n_sel * P.tpf;
+  H.lkv = H.hist_tokens + P.q_tokens;
+  H.k_pool = P.k_pool;
+  H.v_pool = P.v_pool;
+  H.k_cur = P.k_cur + (size_t)h * P.q_tokens * D;
+  H.v_cur = P.v_cur + (size_t)h * P.q_tokens * D;
+  H.slots = P.sel_slots + (size_t)h * P.max_sel;
+  H.lrow = tid / CPR;
+  H.lchunk = tid % CPR;
+  H.thread_off = (unsigned)((H.lrow * D + H.lchunk * 8) * 2);
+  // Q^T fragments: lane (l32, g) holds, for its query row, d = 16*ks + 8*g .. +7
+  const __bf16 *qh = P.q + (size_t)h * P.q_tokens * D;
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int row = pf_min(it.q0 + (wave * NQB + qb) * 32 + l32, P.q_tokens - 1);
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) qf[qb][ks] = *(const bf16x8 *)(qh + (size_t)row * D + ks * 16 + 8 * g);
+  }
+}
+
+template <int D, int NQB>
+__device__ __forceinline__ void attn_zero(f32x16 (&o)[NQB][D / 32], float (&m_run)[NQB], float (&l_run)[NQB]) {
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    m_run[qb] = -3.0e38f;
+    l_run[qb] = 0.0f;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[qb][db][i] = 0.0f;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Kernel 0: 32 query rows per wave, two workgroups per CU.
+// ---------------------------------------------------------------------------------------------------
+// One work item done with the rescaling loop: set-up, loop, epilogue.
+template <int D, int NQB>
+__device__ __forceinline__ void attn_item_classic(const AttnParams &P, const PfWorkItem &it,
+                                                  __bf16 (*sK)[PF_BK * (D + 8)], __bf16 (*sV)[PF_BK * (D + 32)],
+                                                  int32_t *sFlag) {
+  HeadKV H;
+  bf16x8 qf[NQB][D / 16];
+  attn_setup<D, NQB>(P, it, H, qf);
+  f32x16 o[NQB][D / 32];
+  float m_run[NQB], l_run[NQB];
+  attn_zero<D, NQB>(o, m_run, l_run);
+  classic_loop<D, NQB>(H, it.kt0, it.kt1, qf, o, m_run, l_run, sK, sV, P.scale_log2);
+  attn_epilogue<D, NQB>(P, it, o, m_run, l_run, (float *)&sK[0][0], sFlag);
+}
+
+template <int D>
+__global__ __launch_bounds__(ATT_THREADS, 2) void pf_attn_kernel(AttnParams P) {
+  __shared__ __attribute__((aligned(16))) __bf16 sK[2][PF_BK * (D + 8)];
+  __shared__ __attribute__((aligned(16))) __bf16 sV[2][PF_BK * (D + 32)];
+  __shared__ int32_t sFlag;
+  const PfWorkItem it = P.items[blockIdx.x];
+  if (it.head < 0) return;
+  attn_item_classic<D, 1>(P, it, sK, sV, &sFlag);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Kernel 1: 64 query rows per wave, software-pipelined over 32-key half tiles.
+// ---------------------------------------------------------------------------------------------------
+// One half tile (32 keys) in two scheduling regions, each pairing 16 matrix instructions with vector work:
+//   region 1   S^T of the NEXT 32 keys (K fragments fetched from LDS during the previous call)
+//              || row maxima and the weights of the first 16 current keys; the V^T fragments of the
+//              current keys are fetched meanwhile
+//   region 2   O^T += V^T P^T for the 32 current keys || the weights of the last 16; the K fragments of the
+//              keys after next (PREFETCH) are fetched meanwhile
+// The accumulators are never rescaled here: weights are taken relative to a fixed reference maximum m_ref
+// per row, with 2^60 of headroom.  m_seen tracks the largest score met; a score beyond the headroom is
+// reported and the workgroup redoes its item with m_ref = the exact row maxima.
+template <int D, bool NEXT, bool PREFETCH>
+__device__ __forceinline__ bool pipe_half(f32x16 (&s_cur)[2], f32x16 (&s_next)[2], f32x16 (&o)[2][D / 32],
+                                          const float (&m_ref)[2], float (&m_seen)[2], float (&l_run)[2],
+                                          const bf16x8 (&qf)[2][D / 16], KFrags<D / 16> &kf, const __bf16 *sKpf,
+                                          const __bf16 *sVc, int k_lane, int v_lane, float c, float thr) {
+  constexpr int VS = D + 32, NKS = D / 16, NDB = D / 32;
+  const float mc[2] = {m_ref[0] * c, m_ref[1] * c};
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  bf16x8 pf[2][2];                                  // [chunk][query block]: P^T operands
+  auto exp_chunk = [&](int c2) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      bf16x2 pk[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float p0 = fast_exp2(fmaf(s_cur[qb][8 * c2 + 2 * e], c, -mc[qb]));
+        const float p1 = fast_exp2(fmaf(s_cur[qb][8 * c2 + 2 * e + 1], c, -mc[qb]));
+        pk[e][0] = (__bf16)p0;
+        pk[e][1] = (__bf16)p1;
+        l_run[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk[e], ones, l_run[qb], false);   // sums the rounded weights
+      }
+      const bf16x4 lo = __builtin_shufflevector(pk[0], pk[1], 0, 1, 2, 3);
+      const bf16x4 hi = __builtin_shufflevector(pk[2], pk[3], 0, 1, 2, 3);
+      pf[c2][qb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+  };
+
+  // ---- region 1 ----
+  if (NEXT) kf_wait(kf);
+  VtFrags<NDB> vf[2];
+  vt_issue<VS, NDB>(vf[0], &sVc[v_lane]);
+  vt_issue<VS, NDB>(vf[1], &sVc[v_lane + 16 * VS]);
+  float mx[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    float a = s_cur[qb][0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) a = fmaxf(a, s_cur[qb][i]);
+    mx[qb] = a;                                     // per-lane maximum is enough for the overflow test
+    m_seen[qb] = fmaxf(m_seen[qb], a);
+  }
+  const bool overflow = (mx[0] > m_ref[0] + thr) || (mx[1] > m_ref[1] + thr);
+  if (NEXT) {
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, kf.a[ks]);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        if (ks == 0) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s_next[qb][i] = 0.0f;
+        }
+        s_next[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s_next[qb], 0, 0, 0);
+      }
+    }
+  }
+  exp_chunk(0);
+
+  // ---- region 2 ----
+  vt_wait(vf[0], vf[1]);
+  if (PREFETCH) kf_issue<NKS>(kf, &sKpf[k_lane]);
+  exp_chunk(1);
+#pragma unroll
+  for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      const s16x8 av = __builtin_shufflevector(vf[c2].lo[db], vf[c2].hi[db], 0, 1, 2, 3, 4, 5, 6, 7);
+      const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+        o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[c2][qb], o[qb][db], 0, 0, 0);
+    }
+  return overflow;
+}
+
+template <int D>
+__global__ __launch_bounds__(ATT_THREADS, 1) void pf_attn_pipe_kernel(AttnParams P) {
+  constexpr int NQB = 2;
+  constexpr int BK = PF_BK;
+  constexpr int KS = D + 8, VS = D + 32;
+  constexpr int NKS = D / 16;
+
+  __shared__ __attribute__((aligned(16))) __bf16 sK[3][BK * KS];   // K of tiles kt, kt+1 (being read) and kt+2 (landing)
+  __shared__ __attribute__((aligned(16))) __bf16 sV[2][BK * VS];
+  __shared__ int32_t sFlag;
+  __shared__ int32_t sRedo;
+
+  const PfWorkItem it = P.items[blockIdx.x];
+  if (it.head < 0) return;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, g = lane >> 5;
+  HeadKV H;
+  bf16x8 qf[NQB][NKS];
+  attn_setup<D, NQB>(P, it, H, qf);
+  if (tid == 0) sRedo = 0;
+
+  const int k_lane = l32 * KS + 8 * g;
+  const int v_lane = (4 * g + ((lane & 15) >> 2)) * VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  const float c = P.scale_log2;
+  const float thr = ATT_PIPE_LOG2 / c;
+
+  f32x16 o[NQB][D / 32];
+  float m_ref[NQB], l_run[NQB];
+  float m_seen[NQB] = {-3.0e38f, -3.0e38f};         // largest score met per row (this lane's share of the keys)
+
+  // Attempt 0 takes the reference maxima from the item's first 32 keys.  If a later score outgrows the
+  // headroom (never seen on attention-like inputs), the pass still runs to the end to learn the exact row
+  // maxima, and attempt 1 repeats the item with those: it cannot overflow.
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    float dummy[NQB];
+    attn_zero<D, NQB>(o, dummy, l_run);
+
+    // ---- prologue: K and V of the first tile, K of the second, then S^T of the first 32 keys ----
+    TilePos posK = tile_pos_init(it.kt0, H.hist_tokens, H.n_sel, H.tpf), posV = posK;
+    dma_tile<D, KS>(it.kt0, posK, H, H.k_pool, H.k_cur, sK[0], wave, lane);
+    dma_tile<D, VS>(it.kt0, posV, H, H.v_pool, H.v_cur, sV[0], wave, lane);
+    if (it.kt0 + 1 < it.kt1) {
+      tile_pos_advance(posK, H.n_sel, H.tpf);
+      dma_tile<D, KS>(it.kt0 + 1, posK, H, H.k_pool, H.k_cur, sK[1], wave, lane);
+    }
+    __syncthreads();
+    f32x16 s_a[NQB], s_b[NQB];                     // scores of the current / next 32-key half tile (roles swap)
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s_a[qb][i] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      const bf16x8 a = *(const bf16x8 *)(&sK[0][k_lane + ks * 16]);
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) s_a[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s_a[qb], 0, 0, 0);
+    }
+    KFrags<NKS> kf;                                 // K fragments of the 32 keys after the current ones
+    kf_issue<NKS>(kf, &sK[0][32 * KS + k_lane]);
+    if (attempt == 0) {
+      const int valid0 = H.lkv - it.kt0 * BK;       // >= 1: the first key of a work item always exists
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        float a = -3.0e38f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (8 * (i >> 2) + 4 * g + (i & 3) < valid0) a = fmaxf(a, s_a[qb][i]);
+        m_ref[qb] = partner_max(a);
+      }
+    } else {
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) m_ref[qb] = partner_max(m_seen[qb]);
+    }
+
+    // ---- main loop.  Per 64-key tile kt: first half (keys 0-31) runs while S^T of keys 32-63 is computed,
+    // second half while S^T of the first 32 keys of tile kt+1 is computed.  K of tile kt+2 and V of tile kt+1
+    // are copied global -> LDS meanwhile, into buffers last read one tile ago. ----
+    bool overflow = false;
+    int kt = it.kt0;
+    int kb0 = 0;                                      // K buffer of the current tile: (kt - kt0) % 3
+    for (; kt + 1 < it.kt1; ++kt) {                   // every tile but the last: no ragged tail, a next tile exists
+      const int cb = (kt - it.kt0) & 1;               // V buffer of the current tile
+      const int kb1 = kb0 == 2 ? 0 : kb0 + 1, kb2 = kb1 == 2 ? 0 : kb1 + 1;
+      if (kt + 2 < it.kt1) {
+        tile_pos_advance(posK, H.n_sel, H.tpf);
+        dma_tile<D, KS>(kt + 2, posK, H, H.k_pool, H.k_cur, sK[kb2], wave, lane);
+      }
+      tile_pos_advance(posV, H.n_sel, H.tpf);
+      dma_tile<D, VS>(kt + 1, posV, H, H.v_pool, H.v_cur, sV[cb ^ 1], wave, lane);
+      __builtin_amdgcn_sched_barrier(0);              // the two halves are scheduled on their own: short live ranges
+      overflow |= pipe_half<D, true, true>(s_a, s_b, o, m_ref, m_seen, l_run, qf, kf, &sK[kb1][0], &sV[cb][0], k_lane, v_lane, c, thr);
+      __builtin_amdgcn_sched_barrier(0);
+      overflow |= pipe_half<D, true, true>(s_b, s_a, o, m_ref, m_seen, l_run, qf, kf, &sK[kb1][32 * KS], &sV[cb][32 * VS], k_lane, v_lane, c, thr);
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();                                // tiles kt+2 (K) and kt+1 (V) have landed; tile kt is dead
+      kb0 = kb1;
+    }
+    {                                                 // last tile: ragged tail possible, nothing follows
+      const int cb = (kt - it.kt0) & 1;
+      const int kb1 = kb0 == 2 ? 0 : kb0 + 1;
+      const int valid = H.lkv - kt * BK;
+      if (valid < BK) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          if (8 * (i >> 2) + 4 * g + (i & 3) >= valid) {
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) s_a[qb][i] = -INFINITY;
+          }
+        }
+      }
+      overflow |= pipe_half<D, true, false>(s_a, s_b, o, m_ref, m_seen, l_run, qf, kf, &sK[kb1][0], &sV[cb][0], k_lane, v_lane, c, thr);
+      if (valid < BK) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          if (32 + 8 * (i >> 2) + 4 * g + (i & 3) >= valid) {
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) s_b[qb][i] = -INFINITY;
+          }
+        }
+      }
+      overflow |= pipe_half<D, false, false>(s_b, s_a, o, m_ref, m_seen, l_run, qf, kf, &sK[kb1][0], &sV[cb][32 * VS], k_lane, v_lane, c, thr);
+    }
+    if (attempt == 1) break;
+    if (__builtin_amdgcn_ballot_w64(overflow) != 0 && lane == 0) sRedo = 1;
+    __syncthreads();
+    if (!sRedo) break;                                // uniform across the workgroup: read after the barrier
+  }
+  attn_epilogue<D, NQB>(P, it, o, m_ref, l_run, (float *)&sK[0][0], &sFlag);
+}
+
+static int launch_attn(const AttnParams &P, int head_dim, int variant, int n_blocks, hipStream_t stream) {
+  if (head_dim == 128 && variant == 1)
+    hipLaunchKernelGGL((pf_attn_pipe_kernel<128>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
+  else if (head_dim == 128 && variant == 0)
+    hipLaunchKernelGGL((pf_attn_kernel<128>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
+  else if (head_dim == 64 && variant == 0)
+    hipLaunchKernelGGL((pf_attn_kernel<64>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
+  else
+    return PF_ERR_UNSUPPORTED;                      // the pipelined kernel exists for head_dim 128 only
   return hipGetLastError() == hipSuccess ? PF_OK : PF_ERR_HIP;
 }
 
@@ -455,7 +834,5 @@ extern "C" int pf_ragged_attn_fwd(const pf_pool *pool, const pf_index *index, co
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)pool->head_dim);
   P.scale_log2 = scale * 1.4426950408889634f;
   hipStream_t st = (hipStream_t)stream;
-  if (pool->head_dim == 128)
-    return index->variant == 1 ? launch_attn<128, 2>(P, index->n_blocks, st) : launch_attn<128, 1>(P, index->n_blocks, st);
-  return index->variant == 1 ? launch_attn<64, 2>(P, index->n_blocks, st) : launch_attn<64, 1>(P, index->n_blocks, st);
+  return launch_attn(P, pool->head_dim, index->variant, index->n_blocks, st);
 }

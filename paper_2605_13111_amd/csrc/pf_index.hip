@@ -191,7 +191,7 @@ extern "C" int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens
   if (((uintptr_t)index->work) & 15u) return PF_ERR_INVALID_ARG;
   if (index->seg_tiles < 0) return PF_ERR_INVALID_ARG;
 
-  const int variant = pf_resolve_variant();
+  const int variant = pf_resolve_variant(pool->head_dim);
   const int seg_tiles = pf_resolve_seg_tiles(index->seg_tiles);
   int n_teams, n_blocks, n_partials, max_sel_needed;
   pf_host_plan(pool, pool->T_host, q_tokens, variant, seg_tiles, &n_teams, &n_blocks, &n_partials, &max_sel_needed);

@@ -17,6 +17,7 @@ constexpr int PF_MAX_SEL = 1024;        // slot table kept in LDS by the attenti
 constexpr int PF_MAX_HEADS = 1024;      // one index-kernel thread per head
 constexpr int PF_NUM_XCD = 8;           // MI355X: 8 accelerator dies, workgroup i runs on die i % 8
 constexpr int PF_NUM_VARIANTS = 2;
+constexpr int PF_DEFAULT_VARIANT = 0;
 
 // query rows per workgroup of kernel variant v (4 waves x 32 rows x (v+1) row blocks)
 PF_HD int pf_variant_bq(int variant) { return variant == 1 ? 256 : 128; }
@@ -134,7 +135,7 @@ PF_HD size_t pf_partial_bytes(int bq, int head_dim) { return (size_t)bq * (head_
 // ---- host helpers ---------------------------------------------------------------------------
 int pf_validate_pool(const pf_pool *pool);                 // PF_OK or error
 int pf_resolve_seg_tiles(int seg_tiles);                   // 0 -> default, else clamped to the minimum
-int pf_resolve_variant(void);                              // kernel variant in use
+int pf_resolve_variant(int head_dim);                      // kernel variant in use
 // Host plan for the pool's current T: per-launch block count and partial count.
 void pf_host_plan(const pf_pool *pool, int T, int q_tokens, int variant, int seg_tiles,
                   int *n_teams, int *n_blocks, int *n_partials, int *max_sel_needed);
