@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--cpu-rows", type=int, default=192, help="query rows per head of layer 0 timed on the CPU oracle")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="also run one plain device-to-device copy of this many MiB (a dispatch of known size "
+                         "against which hardware traffic counters are scaled)")
     return ap.parse_args()
 
 
@@ -111,6 +114,13 @@ def main():
             if events is not None:
                 e1.record()
                 events.append((e0, e1))
+
+    if args.copy_probe > 0:
+        src = torch.empty(args.copy_probe << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -76,8 +76,10 @@ __global__ __launch_bounds__(INDEX_THREADS) void pf_build_index_kernel(IndexPara
   const int32_t *ids = staged ? s_ids : P.frame_ids;
   const float *scores = staged ? s_scores : P.frame_score;
 
-  // ---- selection: one thread per head walks the head's resident frames (ascending ids) ----
-  for (int h = tid; h < P.n_heads; h += INDEX_THREADS) {
+  // ---- selection: one wave per head, one lane per resident frame (ascending ids, 64 at a time); a lane
+  // decides whether its frame is attended, the wave compacts the survivors with a ballot ----
+  const int lane = tid & 63, wave = tid >> 6;
+  for (int h = wave; h < P.n_heads; h += INDEX_THREADS / 64) {
     const pf_head_policy pol = P.policy[h];
     const int base = P.slot_base[h];
     const int n_res = P.n_frames[h];
@@ -85,33 +87,42 @@ __global__ __launch_bounds__(INDEX_THREADS) void pf_build_index_kernel(IndexPara
     const bool need_rank = pol.type == PF_ANCHOR && pol.mode == PF_MODE_TOPK && pol.cap > 0 &&
                            pf_middle_count(P.T, pol.sink, pol.recent) > pol.cap;
     int n = 0;
-    for (int j = 0; j < n_res; ++j) {
-      const int f = ids[base + j];
-      int rank = 0;
-      if (need_rank && f >= mid_lo && f < mid_hi) {
-        const float sc = scores[base + j];
-        for (int g = 0; g < n_res; ++g) {
-          const int fg = ids[base + g];
-          if (fg < mid_lo || fg >= mid_hi) continue;
-          const float sg = scores[base + g];
-          rank += (sg > sc || (sg == sc && fg < f)) ? 1 : 0;
+    for (int j0 = 0; j0 < n_res; j0 += 64) {
+      const int j = j0 + lane;
+      bool sel = false;
+      int f = -1;
+      if (j < n_res) {
+        f = ids[base + j];
+        int rank = 0;
+        if (need_rank && f >= mid_lo && f < mid_hi) {
+          const float sc = scores[base + j];
+          for (int g = 0; g < n_res; ++g) {
+            const int fg = ids[base + g];
+            if (fg < mid_lo || fg >= mid_hi) continue;
+            const float sg = scores[base + g];
+            rank += (sg > sc || (sg == sc && fg < f)) ? 1 : 0;
+          }
         }
+        sel = frame_selected(pol, P.T, f, rank);
       }
-      if (!frame_selected(pol, P.T, f, rank)) continue;
-      if (n < P.max_sel) {
-        P.sel_frames[(size_t)h * P.max_sel + n] = f;
-        P.sel_slots[(size_t)h * P.max_sel + n] = base + j;
+      const unsigned long long mask = __builtin_amdgcn_ballot_w64(sel);
+      const int pos = n + __builtin_popcountll(mask & ((1ull << lane) - 1ull));
+      if (sel && pos < P.max_sel) {
+        P.sel_frames[(size_t)h * P.max_sel + pos] = f;
+        P.sel_slots[(size_t)h * P.max_sel + pos] = base + j;
       }
-      ++n;
+      n += __builtin_popcountll(mask);
     }
-    P.sel_count[h] = n;
-    s_selcount[h] = n;
-    // The host sized the launch from the closed-form count; a mismatch means the pool does not hold
-    // what the policy asks for (it was not filled through pf_cache_append).
-    if (n != pf_sel_count_impl(pol, P.T) || n > P.max_sel) atomicExch(&s_error, 1);
-    const PfHeadPlan hp = pf_plan_head(n * P.tpf + P.q_tokens, P.seg_tiles);
-    s_nseg[h] = hp.nseg;
-    s_nkvt[h] = hp.n_kvt;
+    if (lane == 0) {
+      P.sel_count[h] = n;
+      s_selcount[h] = n;
+      // The host sized the launch from the closed-form count; a mismatch means the pool does not hold
+      // what the policy asks for (it was not filled through pf_cache_append).
+      if (n != pf_sel_count_impl(pol, P.T) || n > P.max_sel) atomicExch(&s_error, 1);
+      const PfHeadPlan hp = pf_plan_head(n * P.tpf + P.q_tokens, P.seg_tiles);
+      s_nseg[h] = hp.nseg;
+      s_nkvt[h] = hp.n_kvt;
+    }
   }
   for (int i = tid; i < P.n_heads * P.n_qt; i += INDEX_THREADS) P.counters[i] = 0;
   __syncthreads();

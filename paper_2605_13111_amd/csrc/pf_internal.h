@@ -12,7 +12,7 @@
 // ---- tiling constants of the attention kernel ------------------------------------------------
 constexpr int PF_BK = 64;               // keys per tile
 constexpr int PF_MIN_SEG_TILES = 16;    // smallest allowed key-tile count per work item
-constexpr int PF_DEFAULT_SEG_TILES = 64;
+constexpr int PF_DEFAULT_SEG_TILES = 128;
 constexpr int PF_MAX_SEL = 1024;        // slot table kept in LDS by the attention kernel
 constexpr int PF_MAX_HEADS = 1024;      // one index-kernel thread per head
 constexpr int PF_NUM_XCD = 8;           // MI355X: 8 accelerator dies, workgroup i runs on die i % 8
