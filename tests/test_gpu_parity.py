@@ -50,6 +50,14 @@ def test_peaked_logits(variant):
     print("peaked max-abs %.2e rel %.2e" % (a, r))
 
 
+def test_scores_far_above_the_first_keys(variant):
+    """Queries x64: later keys beat the first 32 keys of a work item by far more than 2^60 in the exponent, which
+    makes the pipelined kernel give up its fixed reference maximum and redo the item with the exact row maxima
+    (the other kernel just rescales)."""
+    a, r = G.run_case(_mixed(12), 48, 128, [3, 3, 3, 3], 200, seed=15, q_gain=64.0, seg_tiles=16, label="huge")
+    print("huge logits max-abs %.2e rel %.2e" % (a, r))
+
+
 def test_explicit_scale_and_small_inputs(variant):
     """Explicit softmax scale; second reading of the one-layer workload: tensors scaled by 1/sqrt(128)."""
     G.run_case(_mixed(9), 24, 128, [3, 3, 3], 130, seed=6, scale=0.37, label="scale")
