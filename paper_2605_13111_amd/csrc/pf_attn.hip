@@ -150,11 +150,11 @@ __device__ __forceinline__ void attn_store_rows(const u32x4 (&reg)[NP], __bf16 *
 // each wave moves 16 rows, one 256-byte row per instruction (lane i carries 4 bytes to row start + 4*i), so
 // rows keep their padded LDS stride.  The data lands asynchronously; the barrier that ends the iteration
 // (preceded by the wait for outstanding vector-memory operations) publishes it.
-template <int D, int STRIDE>
+template <int D, int STRIDE, int NWAVES = ATT_WAVES>
 __device__ __forceinline__ void dma_tile(int kt, TilePos pos, const HeadKV &H, const __bf16 *pool, const __bf16 *cur,
                                          __bf16 *sdst, int wave, int lane) {
   static_assert(D == 128, "one row = 64 lanes x 4 bytes");
-  constexpr int ROWS = PF_BK / ATT_WAVES;
+  constexpr int ROWS = PF_BK / NWAVES;
   typedef const __attribute__((address_space(1))) void *gptr_t;
   typedef __attribute__((address_space(3))) void *lptr_t;
   const int last = H.lkv - 1 - kt * PF_BK;
@@ -180,6 +180,46 @@ __device__ __forceinline__ void dma_tile(int kt, TilePos pos, const HeadKV &H, c
       __builtin_amdgcn_global_load_lds((gptr_t)b, (lptr_t)(sdst + row * STRIDE), 4, 0, 0);
     }
   }
+}
+
+// The same copy, one row at a time, so that the copy instructions can be spread between the matrix
+// instructions of a tile instead of queueing up in front of them (a burst of 16 stalls the wave until the
+// memory pipeline has accepted all of them).
+struct TileSrc {
+  bool simple;            // tile inside one frame (or the chunk) and not ragged: base + row * D
+  const __bf16 *kb, *vb;  // first row of the tile (simple case)
+  int kt;
+};
+__device__ __forceinline__ TileSrc tile_src(int kt, TilePos pos, const HeadKV &H, int D) {
+  TileSrc t;
+  const int last = H.lkv - 1 - kt * PF_BK;
+  const bool in_hist = pos.j < H.n_sel;
+  t.simple = last >= PF_BK - 1 && (!in_hist || pos.r + PF_BK <= H.tpf);
+  t.kt = kt;
+  size_t e = 0;
+  if (t.simple) e = in_hist ? ((size_t)H.slots[pos.j] * H.tpf + pos.r) * D : (size_t)pos.r * D;
+  t.kb = (in_hist ? H.k_pool : H.k_cur) + e;
+  t.vb = (in_hist ? H.v_pool : H.v_cur) + e;
+  return t;
+}
+template <int D, int STRIDE, bool IS_V>
+__device__ __forceinline__ void dma_row(const TileSrc &t, const HeadKV &H, int row, __bf16 *sdst, int lane) {
+  typedef const __attribute__((address_space(1))) void *gptr_t;
+  typedef __attribute__((address_space(3))) void *lptr_t;
+  const __bf16 *b;
+  if (t.simple) {
+    b = (IS_V ? t.vb : t.kb) + (size_t)row * D + lane * 2;
+  } else {
+    const int last = H.lkv - 1 - t.kt * PF_BK;
+    const int tk = t.kt * PF_BK + pf_min(row, last);            // rows past the end re-read the last key
+    const bool in_chunk = tk >= H.hist_tokens;
+    const int th = in_chunk ? 0 : tk;
+    const int j = th / H.tpf;
+    const size_t e_hist = ((size_t)pf_max(H.slots[j], 0) * H.tpf + (th - j * H.tpf)) * D;
+    const size_t e = in_chunk ? (size_t)(tk - H.hist_tokens) * D : e_hist;
+    b = (in_chunk ? (IS_V ? H.v_cur : H.k_cur) : (IS_V ? H.v_pool : H.k_pool)) + e + lane * 2;
+  }
+  __builtin_amdgcn_global_load_lds((gptr_t)b, (lptr_t)(sdst + row * STRIDE), 4, 0, 0);
 }
 
 // V^T operand of O^T += V^T P^T for 16 keys x 32 channels: two LDS transpose reads whose row choice
@@ -219,6 +259,19 @@ __device__ __forceinline__ void kf_issue(KFrags<NKS> &f, const __bf16 *kp) {
   const unsigned addr = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) __bf16 *)kp;
 #pragma unroll
   for (int k = 0; k < NKS; ++k) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.a[k]) : "v"(addr), "n"(k * 32));
+}
+// Counted waits: LDS operations of a wave complete in order, so "at most N outstanding" means everything
+// issued before the last N has arrived.
+template <int N>
+__device__ __forceinline__ void kf_wait_n(KFrags<4> &f) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void vt_wait_n(VtFrags<4> &f) {
+  asm volatile("s_waitcnt lgkmcnt(%8)"
+               : "+v"(f.lo[0]), "+v"(f.lo[1]), "+v"(f.lo[2]), "+v"(f.lo[3]), "+v"(f.hi[0]), "+v"(f.hi[1]), "+v"(f.hi[2]),
+                 "+v"(f.hi[3])
+               : "n"(N));
 }
 __device__ __forceinline__ void kf_wait(KFrags<8> &f) {
   asm volatile("s_waitcnt lgkmcnt(0)"
@@ -370,10 +423,11 @@ __device__ __forceinline__ void classic_loop(const HeadKV &H, int kt0, int kt1, 
 // unnormalised partial (O, m, l) and the last segment to arrive merges all partials of its (head, query tile).
 // sScratch: at least 2*BQ floats of LDS that no wave reads any more (every wave passed the loop's last barrier).
 // ---------------------------------------------------------------------------------------------------
-template <int D, int NQB>
+template <int D, int NQB, int NWAVES = ATT_WAVES>
 __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkItem &it, f32x16 (&o)[NQB][D / 32],
                                               float (&m_run)[NQB], float (&l_run)[NQB], float *sScratch, int32_t *sFlagp) {
-  constexpr int BQ = ATT_WAVES * 32 * NQB;
+  constexpr int BQ = NWAVES * 32 * NQB;
+  constexpr int NT = NWAVES * 64;
   constexpr int NDB = D / 32;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -440,7 +494,7 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
   const float *base = P.workspace + (size_t)it.part0 * part_floats;
   const size_t seg_stride = (size_t)P.n_qt * part_floats;
   const int nseg = it.nseg;
-  for (int r = tid; r < BQ; r += ATT_THREADS) {
+  for (int r = tid; r < BQ; r += NT) {
     const float *pm = base + (size_t)BQ * D + r;
     float mmax = -3.0e38f;
 #pragma unroll 8
@@ -455,14 +509,14 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
   __syncthreads();
   __bf16 *oh = P.out + (size_t)h * P.q_tokens * D;
   constexpr int EG = 4;                                        // output quads per thread in flight
-  static_assert((BQ * (D / 4)) % (ATT_THREADS * EG) == 0, "merge tiling");
-  for (int e0 = tid; e0 < BQ * (D / 4); e0 += ATT_THREADS * EG) {
+  static_assert((BQ * (D / 4)) % (NT * EG) == 0, "merge tiling");
+  for (int e0 = tid; e0 < BQ * (D / 4); e0 += NT * EG) {
     int r[EG], dc[EG];
     float mrow[EG];
     float4 acc[EG];
 #pragma unroll
     for (int k = 0; k < EG; ++k) {
-      const int e = e0 + k * ATT_THREADS;
+      const int e = e0 + k * NT;
       r[k] = e / (D / 4);
       dc[k] = (e % (D / 4)) * 4;
       mrow[k] = sM[r[k]];
@@ -784,15 +838,203 @@ __global__ __launch_bounds__(ATT_THREADS, 1) void pf_attn_pipe_kernel(AttnParams
   attn_epilogue<D, NQB>(P, it, o, m_ref, l_run, (float *)&sK[0][0], &sFlag);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Kernel 1 (default for head_dim 128): 8 waves x 32 query rows (BQ = 256), one workgroup per CU, K/V tiles in a
+// 4-stage LDS ring filled by direct global -> LDS copies issued three tiles ahead.  The copies use no
+// registers and no LDS-write instructions, are waited for with a counted s_waitcnt (the copies of the next
+// tiles stay in flight), and each tile is fetched once for 256 query rows.  LDS fragment reads are issued by
+// hand (the compiler would wait for ALL outstanding copies before any LDS read it knows about), a few
+// fragments ahead of the MFMAs that consume them.  Softmax as in the rescaling loop.
+// ---------------------------------------------------------------------------------------------------
+constexpr int RING_WAVES = 8;
+constexpr int RING_STAGES = 4;
+
+template <int D>
+__global__ __launch_bounds__(RING_WAVES * 64, 2) void pf_attn_ring_kernel(AttnParams P) {
+  static_assert(D == 128, "direct global -> LDS rows are 64 lanes x 4 bytes");
+  constexpr int BK = PF_BK;
+  constexpr int KS = D + 8, VS = D + 32;
+  constexpr int NKS = D / 16, NDB = D / 32;
+  constexpr int DMA_PER_TILE = 2 * (BK / RING_WAVES);          // copy instructions per wave per tile (K + V)
+  static_assert(2 * DMA_PER_TILE <= 63, "vmcnt field");
+
+  __shared__ __attribute__((aligned(16))) __bf16 sK[RING_STAGES][BK * KS];
+  __shared__ __attribute__((aligned(16))) __bf16 sV[RING_STAGES][BK * VS];
+  __shared__ int32_t sFlag;
+
+  const PfWorkItem it = P.items[blockIdx.x];
+  if (it.head < 0) return;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, g = lane >> 5;
+  HeadKV H;
+  bf16x8 qf[1][NKS];
+  attn_setup<D, 1>(P, it, H, qf);
+  f32x16 o[1][NDB];
+  float m_run[1], l_run[1];
+  attn_zero<D, 1>(o, m_run, l_run);
+  const int k_lane = l32 * KS + 8 * g;
+  const int v_lane = (4 * g + ((lane & 15) >> 2)) * VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  const float c = P.scale_log2;
+  const float thr = ATT_LAZY_LOG2 / c;
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+
+  // ---- prologue: the first three tiles start travelling ----
+  TilePos pos = tile_pos_init(it.kt0, H.hist_tokens, H.n_sel, H.tpf);
+#pragma unroll
+  for (int a = 0; a < RING_STAGES - 1; ++a) {
+    if (it.kt0 + a < it.kt1) {
+      if (a > 0) tile_pos_advance(pos, H.n_sel, H.tpf);
+      dma_tile<D, KS, RING_WAVES>(it.kt0 + a, pos, H, H.k_pool, H.k_cur, sK[a], wave, lane);
+      dma_tile<D, VS, RING_WAVES>(it.kt0 + a, pos, H, H.v_pool, H.v_cur, sV[a], wave, lane);
+    }
+  }
+
+  int st = 0;                                                  // ring stage of the current tile
+  for (int kt = it.kt0; kt < it.kt1; ++kt) {
+    // this wave's copies of tile kt have landed once at most the copies of the tiles after it are outstanding
+    const int ahead = pf_min(it.kt1 - 1 - kt, RING_STAGES - 2);
+    if (ahead >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (((2 * DMA_PER_TILE) & 15)) | (((2 * DMA_PER_TILE) >> 4) << 14));
+    else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | ((DMA_PER_TILE & 15)) | ((DMA_PER_TILE >> 4) << 14));
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();                              // everyone's rows of tile kt landed; tile kt-1 is dead
+    // the stage tile kt-1 lived in is refilled with tile kt+3, two rows at a time between the MFMA groups below
+    const bool refill = kt + RING_STAGES - 1 < it.kt1;
+    const int sn = (st + RING_STAGES - 1) & (RING_STAGES - 1);
+    TileSrc src;
+    if (refill) {
+      tile_pos_advance(pos, H.n_sel, H.tpf);
+      src = tile_src(kt + RING_STAGES - 1, pos, H, D);
+    }
+    constexpr int RPW = BK / RING_WAVES;                        // rows per wave and tensor
+    auto copy_k = [&](int r2) {
+      if (!refill) return;
+      dma_row<D, KS, false>(src, H, wave * RPW + 2 * r2, sK[sn], lane);
+      dma_row<D, KS, false>(src, H, wave * RPW + 2 * r2 + 1, sK[sn], lane);
+    };
+    auto copy_v = [&](int r2) {
+      if (!refill) return;
+      dma_row<D, VS, true>(src, H, wave * RPW + 2 * r2, sV[sn], lane);
+      dma_row<D, VS, true>(src, H, wave * RPW + 2 * r2 + 1, sV[sn], lane);
+    };
+    const __bf16 *tK = &sK[st][k_lane];
+    const __bf16 *tV = &sV[st][v_lane];
+
+    // ---- S^T = K Q^T: four groups of four K fragments, two groups in flight ----
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[kb][i] = 0.0f;
+    KFrags<4> ka, kb_;
+    VtFrags<NDB> va, vb;
+    kf_issue<4>(ka, tK);
+    kf_issue<4>(kb_, tK + 4 * 16);
+    kf_wait_n<4>(ka);
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka.a[k]), qf[0][k], s[0], 0, 0, 0);
+    copy_k(0);
+    kf_issue<4>(ka, tK + 32 * KS);
+    kf_wait_n<4>(kb_);
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb_.a[k]), qf[0][4 + k], s[0], 0, 0, 0);
+    copy_k(1);
+    kf_issue<4>(kb_, tK + 32 * KS + 4 * 16);
+    kf_wait_n<4>(ka);
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka.a[k]), qf[0][k], s[1], 0, 0, 0);
+    copy_k(2);
+    vt_issue<VS, NDB>(va, tV);
+    kf_wait_n<8>(kb_);
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb_.a[k]), qf[0][4 + k], s[1], 0, 0, 0);
+    copy_k(3);
+    vt_issue<VS, NDB>(vb, tV + 16 * VS);
+
+    const int valid = H.lkv - kt * BK;                          // ragged tail: only the head's last tile
+    if (valid < BK) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3) >= valid) s[kb][i] = -INFINITY;
+    }
+
+    // ---- online softmax with deferred rescaling (see the rescaling loop) ----
+    float mx = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+    mx = partner_max(mx);
+    if (__builtin_amdgcn_ballot_w64(mx > m_run[0] + thr) != 0) {
+      const float m_new = fmaxf(m_run[0], mx);
+      const float alpha = fast_exp2((m_run[0] - m_new) * c);
+      m_run[0] = m_new;
+      l_run[0] *= alpha;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[0][db][i] *= alpha;
+    }
+    const float mc = m_run[0] * c;
+    bf16x8 pf[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        bf16x2 pk;
+        pk[0] = (__bf16)fast_exp2(fmaf(s[kb][i], c, -mc));
+        pk[1] = (__bf16)fast_exp2(fmaf(s[kb][i + 1], c, -mc));
+        l_run[0] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run[0], false);
+        pf[kb * 2 + (i >> 3)][i & 7] = pk[0];
+        pf[kb * 2 + (i >> 3)][(i & 7) + 1] = pk[1];
+      }
+
+    // ---- O^T += V^T P^T: four 16-key chunks, two chunks of V^T fragments in flight ----
+    auto pv = [&](VtFrags<NDB> &vf, int c4) {
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        const s16x8 av = __builtin_shufflevector(vf.lo[db], vf.hi[db], 0, 1, 2, 3, 4, 5, 6, 7);
+        o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pf[c4], o[0][db], 0, 0, 0);
+      }
+    };
+    vt_wait_n<8>(va);
+    pv(va, 0);
+    copy_v(0);
+    vt_issue<VS, NDB>(va, tV + 32 * VS);
+    vt_wait_n<8>(vb);
+    pv(vb, 1);
+    copy_v(1);
+    vt_issue<VS, NDB>(vb, tV + 48 * VS);
+    vt_wait_n<8>(va);
+    pv(va, 2);
+    copy_v(2);
+    vt_wait_n<0>(vb);
+    pv(vb, 3);
+    copy_v(3);
+    st = (st + 1) & (RING_STAGES - 1);
+  }
+  __syncthreads();                                             // all LDS reads done before the stages are reused
+  attn_epilogue<D, 1, RING_WAVES>(P, it, o, m_run, l_run, (float *)&sK[0][0], &sFlag);
+}
+
 static int launch_attn(const AttnParams &P, int head_dim, int variant, int n_blocks, hipStream_t stream) {
   if (head_dim == 128 && variant == 1)
+    hipLaunchKernelGGL((pf_attn_ring_kernel<128>), dim3(n_blocks), dim3(RING_WAVES * 64), 0, stream, P);
+  else if (head_dim == 128 && variant == 2)
     hipLaunchKernelGGL((pf_attn_pipe_kernel<128>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
   else if (head_dim == 128 && variant == 0)
     hipLaunchKernelGGL((pf_attn_kernel<128>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
   else if (head_dim == 64 && variant == 0)
     hipLaunchKernelGGL((pf_attn_kernel<64>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
   else
-    return PF_ERR_UNSUPPORTED;                      // the pipelined kernel exists for head_dim 128 only
+    return PF_ERR_UNSUPPORTED;                      // kernels 1 and 2 exist for head_dim 128 only
   return hipGetLastError() == hipSuccess ? PF_OK : PF_ERR_HIP;
 }
 
