@@ -104,7 +104,10 @@ __device__ __forceinline__ void tile_pos_advance(TilePos &p, int n_sel, int tpf)
 
 struct HeadKV {     // everything a loader thread needs to find keys of one head
   const __bf16 *k_pool, *v_pool, *k_cur, *v_cur;
-  const int32_t *slots;
+  // slot table of the head: written by the index kernel before this launch and constant during it, so it is
+  // read through the constant address space (wave-uniform indices become scalar loads, which do not queue
+  // behind outstanding vector-memory operations)
+  const __attribute__((address_space(4))) int32_t *slots;
   int n_sel, tpf, hist_tokens, lkv;
   int lrow, lchunk;
   unsigned thread_off;
@@ -564,7 +567,7 @@ __device__ __forceinline__ void attn_setup(const AttnParams &P, const PfWorkItem
   H.v_pool = P.v_pool;
   H.k_cur = P.k_cur + (size_t)h * P.q_tokens * D;
   H.v_cur = P.v_cur + (size_t)h * P.q_tokens * D;
-  H.slots = P.sel_slots + (size_t)h * P.max_sel;
+  H.slots = (const __attribute__((address_space(4))) int32_t *)(P.sel_slots + (size_t)h * P.max_sel);
   H.lrow = tid / CPR;
   H.lchunk = tid % CPR;
   H.thread_off = (unsigned)((H.lrow * D + H.lchunk * 8) * 2);
@@ -879,6 +882,11 @@ __global__ __launch_bounds__(RING_WAVES * 64, 2) void pf_attn_ring_kernel(AttnPa
   const float c = P.scale_log2;
   const float thr = ATT_LAZY_LOG2 / c;
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+
+  // Q^T has arrived before the first copy is issued: a wait for it later would also wait for every copy
+  // issued in between (vector-memory operations complete in order)
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[0][ks]));
 
   // ---- prologue: the first three tiles start travelling ----
   TilePos pos = tile_pos_init(it.kt0, H.hist_tokens, H.n_sel, H.tpf);
