@@ -1032,9 +1032,329 @@ __global__ __launch_bounds__(RING_WAVES * 64, 2) void pf_attn_ring_kernel(AttnPa
   attn_epilogue<D, 1, RING_WAVES>(P, it, o, m_run, l_run, (float *)&sK[0][0], &sFlag);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Kernel 3: 8 waves x 32 query rows (BQ = 256) in two groups of four that alternate between a matrix phase
+// and a vector phase.  Waves w and w+4 share a SIMD; group 1 runs one phase behind group 0, so while one
+// wave of a SIMD issues the 32 MFMAs of a tile (O^T += V^T P^T of the previous tile, then S^T = K Q^T of
+// the current one) the other computes its softmax on the vector ALU.  A workgroup barrier ends every phase
+// and keeps the groups in step.
+//   phase M(u)   reads K of tile u and V of tile u-1, issues the copies of tile u+2 into the stage tile u-2
+//                lived in (its last readers, both groups' M(u-1), are two barriers back), and ends with the
+//                wait for this wave's copies of tile u+1
+//   phase V(u)   scores of tile u -> weights (masking of the ragged tail, lazy rescaling as in the
+//                rescaling loop); requests the first V^T fragments of tile u for the next matrix phase
+// K/V tiles travel global -> LDS two tiles ahead into a 4-stage ring with 16-byte copies: one instruction
+// moves four 256-byte rows (lane i -> bytes 16*i of the 1 KB destination), a quarter of the instructions the
+// 4-byte form needs, and the cost of these copies is per instruction.  The destination of such a copy is
+// contiguous, so rows cannot be padded; bank conflicts are avoided by permuting the 16-byte chunks of a row
+// instead, which costs nothing because each lane picks the global chunk it fetches:
+//   K tile   chunk c of row r sits at position c ^ (r & 15)        (16 rows x one chunk = all banks once)
+//   V tile   chunk c of row r sits at position c ^ ((r & 7) << 1)  (the 4 rows of a transpose read land
+//                                                                   in 4 different 32-byte bank groups)
+// ---------------------------------------------------------------------------------------------------
+constexpr int PP_WAVES = 8;
+constexpr int PP_STAGES = 4;
+constexpr int PP_TILE_BYTES = PF_BK * 128 * 2;                  // one tensor's tile, head_dim 128, unpadded
+struct TagT { static constexpr bool value = true; };
+struct TagF { static constexpr bool value = false; };
+template <int N>
+struct IntC { static constexpr int value = N; };
+
+__device__ __forceinline__ int pp_swz(bool is_v, int row) { return is_v ? ((row & 7) << 1) : (row & 15); }
+
+// Copies this wave's 8 rows (wave*8 ..) of tile kt of one tensor into the stage at LDS pointer `stage`.
+// Returns the number of copy instructions issued (2 when the tile is contiguous in memory, else 8).
+// voff[h]: per-lane source offset inside the 4-row group h of this wave, see pp_group_voff.
+template <bool IS_V>
+__device__ __forceinline__ unsigned pp_group_voff(int lane, int row0) {
+  const int rr = lane >> 4, p = lane & 15;
+  return (unsigned)(rr * 256 + ((p ^ pp_swz(IS_V, row0 + rr)) << 4));
+}
+template <bool IS_V>
+__device__ __forceinline__ int pp_copy_rows_slow(int kt, const HeadKV &H, char *stage, int wave, int lane) {
+  typedef const __attribute__((address_space(1))) void *gptr_t;
+  typedef __attribute__((address_space(3))) void *lptr_t;
+  constexpr int D = 128;
+  const int last = H.lkv - 1 - kt * PF_BK;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int row = wave * 8 + r;
+    const int t = kt * PF_BK + pf_min(row, last);                 // rows past the end re-read the last key
+    const bool in_chunk = t >= H.hist_tokens;
+    const int th = in_chunk ? 0 : t;
+    const int j = th / H.tpf;
+    const size_t e_hist = ((size_t)pf_max(H.slots[j], 0) * H.tpf + (th - j * H.tpf)) * D;
+    const size_t e = in_chunk ? (size_t)(t - H.hist_tokens) * D : e_hist;
+    const char *b = (const char *)((in_chunk ? (IS_V ? H.v_cur : H.k_cur) : (IS_V ? H.v_pool : H.k_pool)) + e);
+    const unsigned off = (unsigned)((((lane >> 2) ^ pp_swz(IS_V, row)) << 4) | ((lane & 3) << 2));
+    __builtin_amdgcn_global_load_lds((gptr_t)(b + off), (lptr_t)(stage + row * 256), 4, 0, 0);
+  }
+  return 8;
+}
+
+template <int D>
+__global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams P) {
+  static_assert(D == 128, "tile layouts are written for 256-byte rows");
+  constexpr int BK = PF_BK;
+  constexpr int NKS = D / 16, NDB = D / 32;
+  typedef const __attribute__((address_space(1))) void *gptr_t;
+  typedef __attribute__((address_space(3))) void *lptr_t;
+
+  __shared__ __attribute__((aligned(1024))) char sK[PP_STAGES][PP_TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sV[PP_STAGES][PP_TILE_BYTES];
+  __shared__ int32_t sFlag;
+
+  const PfWorkItem it = P.items[blockIdx.x];
+  if (it.head < 0) return;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2;
+  const int l32 = lane & 31, g = lane >> 5;
+  HeadKV H;
+  bf16x8 qf[1][NKS];
+  attn_setup<D, 1>(P, it, H, qf);
+  f32x16 o[1][NDB];
+  float m_run[1], l_run[1];
+  attn_zero<D, 1>(o, m_run, l_run);
+  const float c = P.scale_log2;
+  const float thr = ATT_LAZY_LOG2 / c;
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+
+  // LDS byte addresses of this lane's fragments inside stage 0 (other stages: + stage * PP_TILE_BYTES).  The
+  // arrays are 1 KB aligned, so the chunk permutation and the k-step / channel-block index act on address
+  // bits nothing else touches and one base register per tensor is enough:
+  //   K: row l32 (+32 per key block), chunk (2*ks + g) ^ (l32 & 15)       -> ak ^ (ks << 5)
+  //   V^T: row 4g + (lane & 15) / 4 (+8, +16 per chunk), chunk (c0 + 4*db) ^ swz  -> av ^ (db << 6)
+  const unsigned ldsK = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char *)&sK[0][0];
+  const unsigned ldsV = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char *)&sV[0][0];
+  const unsigned ak = ldsK + l32 * 256 + ((g ^ (l32 & 15)) << 4);
+  unsigned av;
+  {
+    const int rowv = 4 * g + ((lane & 15) >> 2);
+    const int c0 = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+    av = ldsV + rowv * 256 + ((c0 ^ pp_swz(true, rowv)) << 4) + 8 * (lane & 1);
+  }
+  // per-lane source offsets of this wave's first 4-row copy group; the second group's differ in one bit
+  const unsigned vofK = pp_group_voff<false>(lane, wave * 8), vofV = pp_group_voff<true>(lane, wave * 8);
+
+  // Q^T has arrived before the first copy is issued: a wait for it later would also wait for every copy
+  // issued in between (vector-memory operations complete in order)
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[0][ks]));
+
+  // one 4-row group: h = 0, 1 (K), 2, 3 (V)
+  auto copy_group = [&](const TileSrc &src, int sn, int h) {
+    const int r0 = wave * 8 + 4 * (h & 1);
+    if (h < 2) {
+      const char *b = (const char *)src.kb + r0 * 256;
+      __builtin_amdgcn_global_load_lds((gptr_t)(b + (vofK ^ ((h & 1) << 6))), (lptr_t)(&sK[sn][r0 * 256]), 16, 0, 0);
+    } else {
+      const char *b = (const char *)src.vb + r0 * 256;
+      __builtin_amdgcn_global_load_lds((gptr_t)(b + (vofV ^ ((h & 1) << 7))), (lptr_t)(&sV[sn][r0 * 256]), 16, 0, 0);
+    }
+  };
+  // whole tile at once (prologue, and tiles that cross a frame border or hold the ragged end)
+  auto copy_tile_now = [&](int kt, const TilePos &tp, int sn) -> int {
+    const TileSrc src = tile_src(kt, tp, H, D);
+    if (src.simple) {
+#pragma unroll
+      for (int h = 0; h < 4; ++h) copy_group(src, sn, h);
+      return 4;
+    }
+    pp_copy_rows_slow<false>(kt, H, sK[sn], wave, lane);
+    pp_copy_rows_slow<true>(kt, H, sV[sn], wave, lane);
+    return 16;
+  };
+  // "at most n vector-memory operations outstanding", n one of the per-tile copy counts
+  auto wait_copies = [&](int n) {
+    if (n == 0) __builtin_amdgcn_s_waitcnt(0x0F70);
+    else if (n == 4) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);
+    else __builtin_amdgcn_s_waitcnt(0x0F70 | (16 & 15) | ((16 >> 4) << 14));
+  };
+
+  // ---- prologue: tiles kt0 and kt0+1 start travelling; tile kt0 is waited for ----
+  TilePos pos = tile_pos_init(it.kt0, H.hist_tokens, H.n_sel, H.tpf);
+  copy_tile_now(it.kt0, pos, 0);
+  int n_newest = 0;                                            // copy instructions of the newest tile in flight
+  if (it.kt0 + 1 < it.kt1) {
+    tile_pos_advance(pos, H.n_sel, H.tpf);
+    n_newest = copy_tile_now(it.kt0 + 1, pos, 1);
+  }
+  wait_copies(n_newest);
+  __builtin_amdgcn_s_barrier();
+  if (grp == 1) __builtin_amdgcn_s_barrier();                  // group 1 trails by one phase
+
+  f32x16 s[2];
+  bf16x8 pf[4];
+  KFrags<4> ka, kb_;
+  VtFrags<NDB> va, vb;
+  auto k_issue = [&](KFrags<4> &f, unsigned stage_off, int half, int kb) {   // keys 32*kb.., k-steps 4*half..
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const unsigned a = (ak + stage_off) ^ ((4 * half + k) << 5);
+      if (kb == 0) asm volatile("ds_read_b128 %0, %1" : "=v"(f.a[k]) : "v"(a));
+      else asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(f.a[k]) : "v"(a));
+    }
+  };
+  auto v_issue = [&](VtFrags<NDB> &f, unsigned stage_off, auto c16) {        // 16-key chunk c16 of the tile
+    constexpr int OFF = decltype(c16)::value * 4096;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      const unsigned a = (av + stage_off) ^ (db << 6);
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.lo[db]) : "v"(a), "n"(OFF));
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi[db]) : "v"(a), "n"(OFF + 2048));
+    }
+  };
+
+  // ---- matrix phase: PV of the tile in stage st_pv (fragments of its chunks 0 and 1 already requested),
+  // QK of tile kt in stage st_qk ----
+  auto m_phase = [&](auto has_pv, auto has_qk, int kt, int st_qk, int st_pv) {
+    constexpr bool HAS_PV = decltype(has_pv)::value, HAS_QK = decltype(has_qk)::value;
+    const unsigned offK = st_qk * PP_TILE_BYTES, offV = st_pv * PP_TILE_BYTES;
+    // copies of tile kt+2: the four 4-row groups go out between the MFMA groups below
+    bool inl = false;
+    TileSrc src;
+    src.kb = src.vb = nullptr;
+    const int sn = (st_qk + 2) & (PP_STAGES - 1);
+    int n_sent = 0;
+    if (HAS_QK && kt + 2 < it.kt1) {
+      tile_pos_advance(pos, H.n_sel, H.tpf);
+      src = tile_src(kt + 2, pos, H, D);
+      if (src.simple) {
+        inl = true;
+        n_sent = 4;
+      } else {
+        pp_copy_rows_slow<false>(kt + 2, H, sK[sn], wave, lane);
+        pp_copy_rows_slow<true>(kt + 2, H, sV[sn], wave, lane);
+        n_sent = 16;
+      }
+    }
+    auto copy = [&](int h) {
+      if (inl) copy_group(src, sn, h);
+    };
+    auto pv = [&](VtFrags<NDB> &vf, int c4) {
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        const s16x8 a8 = __builtin_shufflevector(vf.lo[db], vf.hi[db], 0, 1, 2, 3, 4, 5, 6, 7);
+        o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pf[c4], o[0][db], 0, 0, 0);
+      }
+    };
+    auto qk = [&](KFrags<4> &kf, int kb, int half) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf.a[k]), qf[0][4 * half + k], s[kb], 0, 0, 0);
+    };
+
+    if (HAS_PV) {
+      vt_wait_n<8>(va);
+      pv(va, 0);
+      copy(0);
+      v_issue(va, offV, IntC<2>());
+      vt_wait_n<8>(vb);
+      pv(vb, 1);
+      copy(1);
+      v_issue(vb, offV, IntC<3>());
+      if (HAS_QK) k_issue(ka, offK, 0, 0);
+      vt_wait_n<HAS_QK ? 12 : 8>(va);
+      pv(va, 2);
+      copy(2);
+      if (HAS_QK) k_issue(kb_, offK, 1, 0);
+      vt_wait_n<HAS_QK ? 8 : 0>(vb);
+      pv(vb, 3);
+      copy(3);
+    } else {
+      k_issue(ka, offK, 0, 0);
+      k_issue(kb_, offK, 1, 0);
+      copy(0);
+      copy(1);
+      copy(2);
+      copy(3);
+    }
+    if (HAS_QK) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[kb][i] = 0.0f;
+      kf_wait_n<4>(ka);
+      qk(ka, 0, 0);
+      k_issue(ka, offK, 0, 1);
+      kf_wait_n<4>(kb_);
+      qk(kb_, 0, 1);
+      k_issue(kb_, offK, 1, 1);
+      kf_wait_n<4>(ka);
+      qk(ka, 1, 0);
+      kf_wait_n<0>(kb_);
+      qk(kb_, 1, 1);
+      // this wave's rows of tile kt+1 have landed once only the copies of tile kt+2 are outstanding
+      wait_copies(n_sent);
+    }
+    __builtin_amdgcn_s_barrier();
+  };
+
+  // ---- vector phase: scores of tile kt (stage st) -> weights ----
+  auto v_phase = [&](int kt, int st) {
+    v_issue(va, st * PP_TILE_BYTES, IntC<0>());
+    v_issue(vb, st * PP_TILE_BYTES, IntC<1>());
+    const int valid = H.lkv - kt * BK;                          // ragged tail: only the head's last tile
+    if (valid < BK) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3) >= valid) s[kb][i] = -INFINITY;
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+    mx = partner_max(mx);
+    if (__builtin_amdgcn_ballot_w64(mx > m_run[0] + thr) != 0) {
+      const float m_new = fmaxf(m_run[0], mx);
+      const float alpha = fast_exp2((m_run[0] - m_new) * c);
+      m_run[0] = m_new;
+      l_run[0] *= alpha;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[0][db][i] *= alpha;
+    }
+    const float mc = m_run[0] * c;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        bf16x2 pk;
+        pk[0] = (__bf16)fast_exp2(fmaf(s[kb][i], c, -mc));
+        pk[1] = (__bf16)fast_exp2(fmaf(s[kb][i + 1], c, -mc));
+        l_run[0] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run[0], false);
+        pf[kb * 2 + (i >> 3)][i & 7] = pk[0];
+        pf[kb * 2 + (i >> 3)][(i & 7) + 1] = pk[1];
+      }
+    __builtin_amdgcn_s_barrier();
+  };
+
+  int st = 0;
+  m_phase(TagF(), TagT(), it.kt0, 0, 0);
+  v_phase(it.kt0, 0);
+  for (int kt = it.kt0 + 1; kt < it.kt1; ++kt) {
+    const int sp = st;
+    st = (st + 1) & (PP_STAGES - 1);
+    m_phase(TagT(), TagT(), kt, st, sp);
+    v_phase(kt, st);
+  }
+  m_phase(TagT(), TagF(), 0, 0, st);
+  if (grp == 0) __builtin_amdgcn_s_barrier();                  // group 0 waits for group 1's last phase
+  __syncthreads();
+  attn_epilogue<D, 1, PP_WAVES>(P, it, o, m_run, l_run, (float *)&sK[0][0], &sFlag);
+}
+
 static int launch_attn(const AttnParams &P, int head_dim, int variant, int n_blocks, hipStream_t stream) {
   if (head_dim == 128 && variant == 1)
     hipLaunchKernelGGL((pf_attn_ring_kernel<128>), dim3(n_blocks), dim3(RING_WAVES * 64), 0, stream, P);
+  else if (head_dim == 128 && variant == 3)
+    hipLaunchKernelGGL((pf_attn_pp_kernel<128>), dim3(n_blocks), dim3(PP_WAVES * 64), 0, stream, P);
   else if (head_dim == 128 && variant == 2)
     hipLaunchKernelGGL((pf_attn_pipe_kernel<128>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
   else if (head_dim == 128 && variant == 0)

@@ -12,7 +12,7 @@ import gpu_common as G
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=[0, 1, 2], ids=["w4x32", "ring8x32", "pipe4x64"])
+@pytest.fixture(params=[0, 1, 2, 3], ids=["w4x32", "ring8x32", "pipe4x64", "pp8x32"])
 def variant(request):
     old = os.environ.get("PF_ATTN_VARIANT")
     os.environ["PF_ATTN_VARIANT"] = str(request.param)
