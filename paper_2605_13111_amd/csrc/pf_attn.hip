@@ -18,6 +18,7 @@
 // so every lane owns ONE query column: the running maximum and sum of the online softmax live in
 // one register each and need a single exchange with lane^32 per tile.
 #include "pf_internal.h"
+#include <utility>
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
@@ -26,6 +27,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // 16-byte register quad
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
 constexpr int ATT_THREADS = 256;
 constexpr int ATT_WAVES = 4;
@@ -1049,18 +1051,34 @@ __global__ __launch_bounds__(RING_WAVES * 64, 2) void pf_attn_ring_kernel(AttnPa
 // contiguous, so rows cannot be padded; bank conflicts are avoided by permuting the 16-byte chunks of a row
 // instead, which costs nothing because each lane picks the global chunk it fetches:
 //   K tile   chunk c of row r sits at position c ^ (r & 15)        (16 rows x one chunk = all banks once)
-//   V tile   chunk c of row r sits at position c ^ ((r & 7) << 1)  (the 4 rows of a transpose read land
-//                                                                   in 4 different 32-byte bank groups)
+//   V tile   chunk c of row r sits at position c ^ ((r & 3) << 2)  (a transpose read takes 64 bytes from each
+//                                                                   of 4 rows per 32 lanes: 4 x 64 B = all banks once)
 // ---------------------------------------------------------------------------------------------------
 constexpr int PP_WAVES = 8;
-constexpr int PP_STAGES = 4;
+constexpr int PP_KSTAGES = 4;                                   // K of tile u is read in phase M(u)
+constexpr int PP_VSTAGES = 5;                                   // V of tile u is read one phase later, in M(u+1)
 constexpr int PP_TILE_BYTES = PF_BK * 128 * 2;                  // one tensor's tile, head_dim 128, unpadded
 struct TagT { static constexpr bool value = true; };
 struct TagF { static constexpr bool value = false; };
 template <int N>
 struct IntC { static constexpr int value = N; };
+template <int B, class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+  (f(IntC<B + I>()), ...);
+}
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+  static_for_impl<B>(f, std::make_integer_sequence<int, E - B>());
+}
+constexpr int PP_RING = 7;                                      // fragments requested ahead of their MFMA
+// LDS reads that fragments i+1 .. last of a matrix phase take (see the kernel: V^T fragments two, K one)
+constexpr int pp_reads_between(int i, int last) {
+  int n = 0;
+  for (int j = i + 1; j <= last; ++j) n += j < 16 ? 2 : 1;
+  return n;
+}
 
-__device__ __forceinline__ int pp_swz(bool is_v, int row) { return is_v ? ((row & 7) << 1) : (row & 15); }
+__device__ __forceinline__ int pp_swz(bool is_v, int row) { return is_v ? ((row & 3) << 2) : (row & 15); }
 
 // Copies this wave's 8 rows (wave*8 ..) of tile kt of one tensor into the stage at LDS pointer `stage`.
 // Returns the number of copy instructions issued (2 when the tile is contiguous in memory, else 8).
@@ -1092,6 +1110,27 @@ __device__ __forceinline__ int pp_copy_rows_slow(int kt, const HeadKV &H, char *
   return 8;
 }
 
+// Request fragment I of a matrix phase (see the kernel): ak / av = this lane's K / V^T base address in the stage.
+template <int I>
+__device__ __forceinline__ void pp_issue_frag(u32x2 (&vl)[16], u32x2 (&vh)[16], u32x4 (&kf)[16], unsigned ak, unsigned av) {
+  if constexpr (I < 16) {
+    constexpr int OFF = (I / 4) * 4096;
+    const unsigned a = av ^ ((I % 4) << 6);
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vl[I]) : "v"(a), "n"(OFF));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[I]) : "v"(a), "n"(OFF + 2048));
+  } else {
+    constexpr int J = I - 16;
+    const unsigned a = ak ^ ((J >> 1) << 5);
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(kf[J]) : "v"(a), "n"((J & 1) * 8192));
+  }
+}
+template <int I, int LAST>
+__device__ __forceinline__ void pp_wait_frag(u32x2 (&vl)[16], u32x2 (&vh)[16], u32x4 (&kf)[16]) {
+  constexpr int N = pp_reads_between(I, LAST) > 15 ? 15 : pp_reads_between(I, LAST);
+  if constexpr (I < 16) asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(vl[I]), "+v"(vh[I]) : "n"(N));
+  else asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(kf[I - 16]) : "n"(N));
+}
+
 template <int D>
 __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams P) {
   static_assert(D == 128, "tile layouts are written for 256-byte rows");
@@ -1100,8 +1139,8 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   typedef const __attribute__((address_space(1))) void *gptr_t;
   typedef __attribute__((address_space(3))) void *lptr_t;
 
-  __shared__ __attribute__((aligned(1024))) char sK[PP_STAGES][PP_TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sV[PP_STAGES][PP_TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sK[PP_KSTAGES][PP_TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sV[PP_VSTAGES][PP_TILE_BYTES];
   __shared__ int32_t sFlag;
 
   const PfWorkItem it = P.items[blockIdx.x];
@@ -1135,7 +1174,8 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     const int c0 = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
     av = ldsV + rowv * 256 + ((c0 ^ pp_swz(true, rowv)) << 4) + 8 * (lane & 1);
   }
-  // per-lane source offsets of this wave's first 4-row copy group; the second group's differ in one bit
+  // per-lane source offsets of this wave's first 4-row copy group; the second group's (rows + 4) differ in
+  // one bit for K and not at all for V
   const unsigned vofK = pp_group_voff<false>(lane, wave * 8), vofV = pp_group_voff<true>(lane, wave * 8);
 
   // Q^T has arrived before the first copy is issued: a wait for it later would also wait for every copy
@@ -1144,158 +1184,150 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[0][ks]));
 
   // one 4-row group: h = 0, 1 (K), 2, 3 (V)
-  auto copy_group = [&](const TileSrc &src, int sn, int h) {
+  auto copy_group = [&](const TileSrc &src, int snk, int snv, int h) {
     const int r0 = wave * 8 + 4 * (h & 1);
     if (h < 2) {
       const char *b = (const char *)src.kb + r0 * 256;
-      __builtin_amdgcn_global_load_lds((gptr_t)(b + (vofK ^ ((h & 1) << 6))), (lptr_t)(&sK[sn][r0 * 256]), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(b + (vofK ^ ((h & 1) << 6))), (lptr_t)(&sK[snk][r0 * 256]), 16, 0, 0);
     } else {
       const char *b = (const char *)src.vb + r0 * 256;
-      __builtin_amdgcn_global_load_lds((gptr_t)(b + (vofV ^ ((h & 1) << 7))), (lptr_t)(&sV[sn][r0 * 256]), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(b + vofV), (lptr_t)(&sV[snv][r0 * 256]), 16, 0, 0);
     }
   };
   // whole tile at once (prologue, and tiles that cross a frame border or hold the ragged end)
-  auto copy_tile_now = [&](int kt, const TilePos &tp, int sn) -> int {
+  auto copy_tile_now = [&](int kt, const TilePos &tp, int snk, int snv) -> int {
     const TileSrc src = tile_src(kt, tp, H, D);
     if (src.simple) {
 #pragma unroll
-      for (int h = 0; h < 4; ++h) copy_group(src, sn, h);
+      for (int h = 0; h < 4; ++h) copy_group(src, snk, snv, h);
       return 4;
     }
-    pp_copy_rows_slow<false>(kt, H, sK[sn], wave, lane);
-    pp_copy_rows_slow<true>(kt, H, sV[sn], wave, lane);
+    pp_copy_rows_slow<false>(kt, H, sK[snk], wave, lane);
+    pp_copy_rows_slow<true>(kt, H, sV[snv], wave, lane);
     return 16;
   };
-  // "at most n vector-memory operations outstanding", n one of the per-tile copy counts
+  // "at most n vector-memory operations outstanding", n = the copy instructions of the two newest tiles
+  // (0, 4 or 16 each)
   auto wait_copies = [&](int n) {
-    if (n == 0) __builtin_amdgcn_s_waitcnt(0x0F70);
-    else if (n == 4) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);
-    else __builtin_amdgcn_s_waitcnt(0x0F70 | (16 & 15) | ((16 >> 4) << 14));
+    switch (n) {
+      case 4: __builtin_amdgcn_s_waitcnt(0x0F70 | 4); break;
+      case 8: __builtin_amdgcn_s_waitcnt(0x0F70 | 8); break;
+      case 16: __builtin_amdgcn_s_waitcnt(0x0F70 | (16 & 15) | ((16 >> 4) << 14)); break;
+      case 20: __builtin_amdgcn_s_waitcnt(0x0F70 | (20 & 15) | ((20 >> 4) << 14)); break;
+      case 32: __builtin_amdgcn_s_waitcnt(0x0F70 | (32 & 15) | ((32 >> 4) << 14)); break;
+      default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+    }
   };
 
-  // ---- prologue: tiles kt0 and kt0+1 start travelling; tile kt0 is waited for ----
+  // ---- prologue: tiles kt0 .. kt0+2 start travelling; tile kt0 is waited for ----
   TilePos pos = tile_pos_init(it.kt0, H.hist_tokens, H.n_sel, H.tpf);
-  copy_tile_now(it.kt0, pos, 0);
-  int n_newest = 0;                                            // copy instructions of the newest tile in flight
+  copy_tile_now(it.kt0, pos, 0, 0);
+  int n_prev = 0, n_last = 0;                                  // copy instructions of the two newest tiles in flight
   if (it.kt0 + 1 < it.kt1) {
     tile_pos_advance(pos, H.n_sel, H.tpf);
-    n_newest = copy_tile_now(it.kt0 + 1, pos, 1);
+    n_prev = copy_tile_now(it.kt0 + 1, pos, 1, 1);
   }
-  wait_copies(n_newest);
+  if (it.kt0 + 2 < it.kt1) {
+    tile_pos_advance(pos, H.n_sel, H.tpf);
+    n_last = copy_tile_now(it.kt0 + 2, pos, 2, 2);
+  }
+  wait_copies(n_prev + n_last);
   __builtin_amdgcn_s_barrier();
   if (grp == 1) __builtin_amdgcn_s_barrier();                  // group 1 trails by one phase
 
+  // ---- fragments.  A matrix phase consumes 32 operand fragments from LDS, one per MFMA:
+  //   0..15   V^T of the previous tile: 16-key chunk i/4, channel block i%4 (two 8-byte transpose reads)
+  //   16..31  K of the current tile: key block (i-16)%2, k-step (i-16)/2 (one 16-byte read); the two key
+  //           blocks alternate so consecutive MFMAs never wait for each other's accumulator
+  // They are requested PP_RING fragments ahead of their MFMA (at most 15 LDS reads may be in flight per
+  // wave) and waited for with counted waits: LDS reads of a wave complete in order.
   f32x16 s[2];
   bf16x8 pf[4];
-  KFrags<4> ka, kb_;
-  VtFrags<NDB> va, vb;
-  auto k_issue = [&](KFrags<4> &f, unsigned stage_off, int half, int kb) {   // keys 32*kb.., k-steps 4*half..
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const unsigned a = (ak + stage_off) ^ ((4 * half + k) << 5);
-      if (kb == 0) asm volatile("ds_read_b128 %0, %1" : "=v"(f.a[k]) : "v"(a));
-      else asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(f.a[k]) : "v"(a));
-    }
+  u32x2 vl[16], vh[16];
+  u32x4 kf[16];
+  auto issue_frag = [&](auto idx, unsigned offK, unsigned offV) {
+    pp_issue_frag<decltype(idx)::value>(vl, vh, kf, ak + offK, av + offV);
   };
-  auto v_issue = [&](VtFrags<NDB> &f, unsigned stage_off, auto c16) {        // 16-key chunk c16 of the tile
-    constexpr int OFF = decltype(c16)::value * 4096;
-#pragma unroll
-    for (int db = 0; db < NDB; ++db) {
-      const unsigned a = (av + stage_off) ^ (db << 6);
-      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.lo[db]) : "v"(a), "n"(OFF));
-      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi[db]) : "v"(a), "n"(OFF + 2048));
+  // wait until fragment I has arrived, LAST being the newest fragment requested so far
+  auto wait_frag = [&](auto idx, auto last) {
+    pp_wait_frag<decltype(idx)::value, decltype(last)::value>(vl, vh, kf);
+  };
+  auto mfma_frag = [&](auto idx) {
+    constexpr int I = decltype(idx)::value;
+    if constexpr (I < 16) {
+      const u32x4 a4 = __builtin_shufflevector(vl[I], vh[I], 0, 1, 2, 3);
+      o[0][I % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a4), pf[I / 4], o[0][I % 4], 0, 0, 0);
+    } else {
+      constexpr int J = I - 16, KB = J & 1, KSTEP = J >> 1;
+      const f32x16 zero = {};
+      s[KB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[J]), qf[0][KSTEP], KSTEP == 0 ? zero : s[KB], 0, 0, 0);
     }
   };
 
-  // ---- matrix phase: PV of the tile in stage st_pv (fragments of its chunks 0 and 1 already requested),
-  // QK of tile kt in stage st_qk ----
-  auto m_phase = [&](auto has_pv, auto has_qk, int kt, int st_qk, int st_pv) {
-    constexpr bool HAS_PV = decltype(has_pv)::value, HAS_QK = decltype(has_qk)::value;
-    const unsigned offK = st_qk * PP_TILE_BYTES, offV = st_pv * PP_TILE_BYTES;
-    // copies of tile kt+2: the four 4-row groups go out between the MFMA groups below
-    bool inl = false;
-    TileSrc src;
-    src.kb = src.vb = nullptr;
-    const int sn = (st_qk + 2) & (PP_STAGES - 1);
-    int n_sent = 0;
-    if (HAS_QK && kt + 2 < it.kt1) {
+  // ---- plan of the next copy (made in the vector phase, where the scalar load of the frame's slot is off
+  // the matrix path; carried out in the following matrix phase, when the target stages are free) ----
+  TileSrc nsrc;
+  nsrc.kb = nsrc.vb = nullptr;
+  nsrc.simple = false;
+  int ncopy_kt = -1;                                           // tile to copy in the next matrix phase, -1: none
+  auto plan_copy = [&](int kt_target) {
+    ncopy_kt = -1;
+    if (kt_target < it.kt1) {
       tile_pos_advance(pos, H.n_sel, H.tpf);
-      src = tile_src(kt + 2, pos, H, D);
-      if (src.simple) {
+      nsrc = tile_src(kt_target, pos, H, D);
+      ncopy_kt = kt_target;
+    }
+  };
+
+  // ---- matrix phase: PV of the tile whose V sits in stage st_pv (its fragments 0 .. PP_RING-1 already
+  // requested), QK of the tile whose K sits in stage st_qk ----
+  auto m_phase = [&](auto has_pv, auto has_qk, int st_qk, int st_pv) {
+    constexpr bool HAS_PV = decltype(has_pv)::value, HAS_QK = decltype(has_qk)::value;
+    constexpr int FIRST = HAS_PV ? 0 : 16, LAST = HAS_QK ? 31 : 15;
+    const unsigned offK = st_qk * PP_TILE_BYTES, offV = st_pv * PP_TILE_BYTES;
+    // copies of the planned tile (three ahead of the QK tile): K into the stage after next of the K ring (tile
+    // kt-1's), V into the stage before st_pv (tile kt-2's); the four 4-row groups go out between the MFMAs
+    const int snk = (st_qk + 3) & (PP_KSTAGES - 1);
+    const int snv = st_pv >= 1 ? st_pv - 1 : PP_VSTAGES - 1;
+    bool inl = false;
+    int n_sent = 0;
+    if (HAS_QK && ncopy_kt >= 0) {
+      if (nsrc.simple) {
         inl = true;
         n_sent = 4;
       } else {
-        pp_copy_rows_slow<false>(kt + 2, H, sK[sn], wave, lane);
-        pp_copy_rows_slow<true>(kt + 2, H, sV[sn], wave, lane);
+        pp_copy_rows_slow<false>(ncopy_kt, H, sK[snk], wave, lane);
+        pp_copy_rows_slow<true>(ncopy_kt, H, sV[snv], wave, lane);
         n_sent = 16;
       }
     }
-    auto copy = [&](int h) {
-      if (inl) copy_group(src, sn, h);
-    };
-    auto pv = [&](VtFrags<NDB> &vf, int c4) {
-#pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-        const s16x8 a8 = __builtin_shufflevector(vf.lo[db], vf.hi[db], 0, 1, 2, 3, 4, 5, 6, 7);
-        o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pf[c4], o[0][db], 0, 0, 0);
+    if constexpr (!HAS_PV) static_for<16, 16 + PP_RING>([&](auto f) { issue_frag(f, offK, offV); });
+    static_for<FIRST, LAST + 1>([&](auto f) {
+      constexpr int I = decltype(f)::value;
+      constexpr int NEWEST = I + PP_RING - 1 < LAST ? I + PP_RING - 1 : LAST;
+      wait_frag(f, IntC<NEWEST>());
+      mfma_frag(f);
+      if constexpr (I + PP_RING <= LAST) issue_frag(IntC<I + PP_RING>(), offK, offV);
+      if constexpr (HAS_QK && (I - FIRST) % 4 == 3 && (I - FIRST) / 4 < 4) {
+        if (inl) copy_group(nsrc, snk, snv, (I - FIRST) / 4);
       }
-    };
-    auto qk = [&](KFrags<4> &kf, int kb, int half) {
-#pragma unroll
-      for (int k = 0; k < 4; ++k)
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf.a[k]), qf[0][4 * half + k], s[kb], 0, 0, 0);
-    };
-
-    if (HAS_PV) {
-      vt_wait_n<8>(va);
-      pv(va, 0);
-      copy(0);
-      v_issue(va, offV, IntC<2>());
-      vt_wait_n<8>(vb);
-      pv(vb, 1);
-      copy(1);
-      v_issue(vb, offV, IntC<3>());
-      if (HAS_QK) k_issue(ka, offK, 0, 0);
-      vt_wait_n<HAS_QK ? 12 : 8>(va);
-      pv(va, 2);
-      copy(2);
-      if (HAS_QK) k_issue(kb_, offK, 1, 0);
-      vt_wait_n<HAS_QK ? 8 : 0>(vb);
-      pv(vb, 3);
-      copy(3);
-    } else {
-      k_issue(ka, offK, 0, 0);
-      k_issue(kb_, offK, 1, 0);
-      copy(0);
-      copy(1);
-      copy(2);
-      copy(3);
-    }
+      __builtin_amdgcn_sched_barrier(0);                        // keep the hand-made order: wait, MFMA, next request
+    });
     if (HAS_QK) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[kb][i] = 0.0f;
-      kf_wait_n<4>(ka);
-      qk(ka, 0, 0);
-      k_issue(ka, offK, 0, 1);
-      kf_wait_n<4>(kb_);
-      qk(kb_, 0, 1);
-      k_issue(kb_, offK, 1, 1);
-      kf_wait_n<4>(ka);
-      qk(ka, 1, 0);
-      kf_wait_n<0>(kb_);
-      qk(kb_, 1, 1);
-      // this wave's rows of tile kt+1 have landed once only the copies of tile kt+2 are outstanding
-      wait_copies(n_sent);
+      // this wave's rows of the tile after the QK tile have landed once only the copies of the two tiles
+      // behind it are outstanding
+      n_prev = n_last;
+      n_last = n_sent;
+      wait_copies(n_prev + n_last);
     }
     __builtin_amdgcn_s_barrier();
   };
 
-  // ---- vector phase: scores of tile kt (stage st) -> weights ----
-  auto v_phase = [&](int kt, int st) {
-    v_issue(va, st * PP_TILE_BYTES, IntC<0>());
-    v_issue(vb, st * PP_TILE_BYTES, IntC<1>());
+  // ---- vector phase: scores of tile kt -> weights; requests the first V^T fragments of tile kt (V stage
+  // sv) for the next matrix phase and plans that phase's copy ----
+  auto v_phase = [&](int kt, int sv_) {
+    static_for<0, PP_RING>([&](auto f) { issue_frag(f, 0u, (unsigned)(sv_ * PP_TILE_BYTES)); });
+    plan_copy(kt + 4);
     const int valid = H.lkv - kt * BK;                          // ragged tail: only the head's last tile
     if (valid < BK) {
 #pragma unroll
@@ -1335,16 +1367,18 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     __builtin_amdgcn_s_barrier();
   };
 
-  int st = 0;
-  m_phase(TagF(), TagT(), it.kt0, 0, 0);
+  int sk = 0, sv = 0;                                          // K and V stage of the tile whose scores are computed
+  plan_copy(it.kt0 + 3);
+  m_phase(TagF(), TagT(), 0, PP_VSTAGES - 1);                  // "the V stage before tile kt0's"
   v_phase(it.kt0, 0);
   for (int kt = it.kt0 + 1; kt < it.kt1; ++kt) {
-    const int sp = st;
-    st = (st + 1) & (PP_STAGES - 1);
-    m_phase(TagT(), TagT(), kt, st, sp);
-    v_phase(kt, st);
+    const int sp = sv;
+    sk = (sk + 1) & (PP_KSTAGES - 1);
+    sv = sv + 1 == PP_VSTAGES ? 0 : sv + 1;
+    m_phase(TagT(), TagT(), sk, sp);
+    v_phase(kt, sv);
   }
-  m_phase(TagT(), TagF(), 0, 0, st);
+  m_phase(TagT(), TagF(), 0, sv);
   if (grp == 0) __builtin_amdgcn_s_barrier();                  // group 0 waits for group 1's last phase
   __syncthreads();
   attn_epilogue<D, 1, PP_WAVES>(P, it, o, m_run, l_run, (float *)&sK[0][0], &sFlag);
