@@ -1273,8 +1273,17 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   auto plan_copy = [&](int kt_target) {
     ncopy_kt = -1;
     if (kt_target < it.kt1) {
+      const int j_prev = pos.j;
       tile_pos_advance(pos, H.n_sel, H.tpf);
-      nsrc = tile_src(kt_target, pos, H, D);
+      // common case: the tile follows a contiguous tile of the same frame (or of the chunk) and is itself whole
+      // and inside it: both sources move on by one tile, no slot lookup
+      const bool whole = H.lkv - kt_target * PF_BK >= PF_BK && (pos.j >= H.n_sel || pos.r + PF_BK <= H.tpf);
+      if (nsrc.simple && pos.j == j_prev && whole) {
+        nsrc.kb += PF_BK * D;
+        nsrc.vb += PF_BK * D;
+      } else {
+        nsrc = tile_src(kt_target, pos, H, D);
+      }
       ncopy_kt = kt_target;
     }
   };
@@ -1301,6 +1310,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
         n_sent = 16;
       }
     }
+    __builtin_amdgcn_s_setprio(3);                              // the matrix phase goes first on its SIMD
     if constexpr (!HAS_PV) static_for<16, 16 + PP_RING>([&](auto f) { issue_frag(f, offK, offV); });
     static_for<FIRST, LAST + 1>([&](auto f) {
       constexpr int I = decltype(f)::value;
@@ -1313,6 +1323,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
       }
       __builtin_amdgcn_sched_barrier(0);                        // keep the hand-made order: wait, MFMA, next request
     });
+    __builtin_amdgcn_s_setprio(0);
     if (HAS_QK) {
       // this wave's rows of the tile after the QK tile have landed once only the copies of the two tiles
       // behind it are outstanding
