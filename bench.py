@@ -160,7 +160,7 @@ def main():
                    "attn_variant": int(layers[0][1].c.variant),
                    "seg_tiles": int(os.environ.get("PF_SEG_TILES", "0")) or "default"},
         "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
-        "roofline": {"kernel": "pf_attn_kernel", "bound": "mfma", "achieved": round(achieved, 2),
+        "roofline": {"kernel": "pf_attn_pp_kernel" if int(layers[0][1].c.variant) == 1 else "pf_attn_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": None, "avg_launch_ms": round(attn_ms_avg, 4),
                      "flop_per_launch": flops_per_launch, "launches_timed": len(attn_ms)},

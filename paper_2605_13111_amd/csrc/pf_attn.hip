@@ -1,14 +1,12 @@
 // Ragged-cache attention forward (Sec. 4.3; Eq. 1 per head over [selected frames || chunk]).
 //
-// One launch per layer.  A workgroup (4 waves) owns BQ query rows of one head and a run of 64-key tiles of
-// that head's ragged key sequence; heads with many keys are cut into several runs whose partial results
-// are merged by the last workgroup to finish (no spinning).  Two kernels share the layouts below:
-//   pf_attn_kernel       BQ = 128, 32 query rows per wave, two workgroups per CU (the second wave on each
-//                        SIMD hides the first one's softmax)
-//   pf_attn_pipe_kernel  BQ = 256, 64 query rows per wave (every K / V fragment read from LDS feeds two
-//                        MFMAs, halving LDS traffic), one wave per SIMD; S^T of the NEXT 32 keys is computed
-//                        while the softmax of the current 32 runs, so matrix and vector work overlap inside
-//                        one instruction stream
+// One launch per layer.  A workgroup owns BQ query rows of one head and a run of 64-key tiles of that
+// head's ragged key sequence; heads with many keys are cut into several runs whose partial results are
+// merged by the last workgroup to finish (no spinning).  Two kernels share the operand layouts below:
+//   pf_attn_kernel     BQ = 128, 4 waves x 32 query rows, two workgroups per CU, tiles staged through
+//                      registers into padded LDS rows; any head_dim in {64, 128}
+//   pf_attn_pp_kernel  BQ = 256, 8 waves x 32 query rows in two groups that alternate between a matrix phase
+//                      and a vector phase, tiles copied global -> LDS directly; head_dim 128 (the default there)
 //
 // Per tile, on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate):
 //   S^T = K . Q^T     A operand = K rows from LDS, B operand = Q^T held in registers
@@ -32,10 +30,9 @@ typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 constexpr int ATT_THREADS = 256;
 constexpr int ATT_WAVES = 4;
 // Exponent headroom (log2 units) a score may have over the reference maximum before the accumulators
-// must be rescaled: weights stay below 2^8 in the rescaling loop, 2^60 in the pipelined loop (fp32 and
-// bf16 share the 8-bit exponent, so both hold such weights without loss of relative precision).
+// must be rescaled: weights stay below 2^8 (fp32 and bf16 share the 8-bit exponent, so both hold such
+// weights without loss of relative precision).
 constexpr float ATT_LAZY_LOG2 = 8.0f;
-constexpr float ATT_PIPE_LOG2 = 60.0f;
 
 struct AttnParams {
   const __bf16 *q, *k_cur, *v_cur, *k_pool, *v_pool;
@@ -151,45 +148,7 @@ __device__ __forceinline__ void attn_store_rows(const u32x4 (&reg)[NP], __bf16 *
   for (int p = 0; p < NP; ++p) *(u32x4 *)(&dst[(lrow + p * RPP) * STRIDE + lchunk * 8]) = reg[p];
 }
 
-// Global -> LDS copy of one 64-key tile of one tensor WITHOUT passing through registers (head_dim 128 only):
-// each wave moves 16 rows, one 256-byte row per instruction (lane i carries 4 bytes to row start + 4*i), so
-// rows keep their padded LDS stride.  The data lands asynchronously; the barrier that ends the iteration
-// (preceded by the wait for outstanding vector-memory operations) publishes it.
-template <int D, int STRIDE, int NWAVES = ATT_WAVES>
-__device__ __forceinline__ void dma_tile(int kt, TilePos pos, const HeadKV &H, const __bf16 *pool, const __bf16 *cur,
-                                         __bf16 *sdst, int wave, int lane) {
-  static_assert(D == 128, "one row = 64 lanes x 4 bytes");
-  constexpr int ROWS = PF_BK / NWAVES;
-  typedef const __attribute__((address_space(1))) void *gptr_t;
-  typedef __attribute__((address_space(3))) void *lptr_t;
-  const int last = H.lkv - 1 - kt * PF_BK;
-  const bool in_hist = pos.j < H.n_sel;
-  const bool simple = last >= PF_BK - 1 && (!in_hist || pos.r + PF_BK <= H.tpf);
-  if (simple) {
-    const __bf16 *b = in_hist ? pool + ((size_t)H.slots[pos.j] * H.tpf + pos.r) * D : cur + (size_t)pos.r * D;
-    b += (size_t)(wave * ROWS) * D + lane * 2;
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r)
-      __builtin_amdgcn_global_load_lds((gptr_t)(b + r * D), (lptr_t)(sdst + (wave * ROWS + r) * STRIDE), 4, 0, 0);
-  } else {
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r) {
-      const int row = wave * ROWS + r;
-      const int t = kt * PF_BK + pf_min(row, last);               // rows past the end re-read the last key
-      const bool in_chunk = t >= H.hist_tokens;
-      const int th = in_chunk ? 0 : t;
-      const int j = th / H.tpf;
-      const size_t e_hist = ((size_t)pf_max(H.slots[j], 0) * H.tpf + (th - j * H.tpf)) * D;
-      const size_t e = in_chunk ? (size_t)(t - H.hist_tokens) * D : e_hist;
-      const __bf16 *b = (in_chunk ? cur : pool) + e + lane * 2;
-      __builtin_amdgcn_global_load_lds((gptr_t)b, (lptr_t)(sdst + row * STRIDE), 4, 0, 0);
-    }
-  }
-}
-
-// The same copy, one row at a time, so that the copy instructions can be spread between the matrix
-// instructions of a tile instead of queueing up in front of them (a burst of 16 stalls the wave until the
-// memory pipeline has accepted all of them).
+// Where a tile's rows come from, for the direct global -> LDS copies of the two-group kernel.
 struct TileSrc {
   bool simple;            // tile inside one frame (or the chunk) and not ragged: base + row * D
   const __bf16 *kb, *vb;  // first row of the tile (simple case)
@@ -207,26 +166,6 @@ __device__ __forceinline__ TileSrc tile_src(int kt, TilePos pos, const HeadKV &H
   t.vb = (in_hist ? H.v_pool : H.v_cur) + e;
   return t;
 }
-template <int D, int STRIDE, bool IS_V>
-__device__ __forceinline__ void dma_row(const TileSrc &t, const HeadKV &H, int row, __bf16 *sdst, int lane) {
-  typedef const __attribute__((address_space(1))) void *gptr_t;
-  typedef __attribute__((address_space(3))) void *lptr_t;
-  const __bf16 *b;
-  if (t.simple) {
-    b = (IS_V ? t.vb : t.kb) + (size_t)row * D + lane * 2;
-  } else {
-    const int last = H.lkv - 1 - t.kt * PF_BK;
-    const int tk = t.kt * PF_BK + pf_min(row, last);            // rows past the end re-read the last key
-    const bool in_chunk = tk >= H.hist_tokens;
-    const int th = in_chunk ? 0 : tk;
-    const int j = th / H.tpf;
-    const size_t e_hist = ((size_t)pf_max(H.slots[j], 0) * H.tpf + (th - j * H.tpf)) * D;
-    const size_t e = in_chunk ? (size_t)(tk - H.hist_tokens) * D : e_hist;
-    b = (in_chunk ? (IS_V ? H.v_cur : H.k_cur) : (IS_V ? H.v_pool : H.k_pool)) + e + lane * 2;
-  }
-  __builtin_amdgcn_global_load_lds((gptr_t)b, (lptr_t)(sdst + row * STRIDE), 4, 0, 0);
-}
-
 // V^T operand of O^T += V^T P^T for 16 keys x 32 channels: two LDS transpose reads whose row choice
 // (4g+r and 8+4g+r) reproduces the key order of the S^T accumulator registers.
 template <int VS>
@@ -237,61 +176,9 @@ __device__ __forceinline__ bf16x8 read_vt(const __bf16 *vp) {
   return __builtin_bit_cast(bf16x8, av);
 }
 
-// The same V^T operands for one 16-key chunk (all D/32 channel blocks), read with hand-issued instructions.
-// The compiler treats the transpose-read builtin as a possible reader of every outstanding global -> LDS
-// copy and would wait for the copies of the NEXT tiles before each use; issued this way the reads only
-// wait for LDS (vt_wait), and the copies stay in flight for the whole tile.
-template <int NDB>
-struct VtFrags {
-  s16x4 lo[NDB], hi[NDB];
-};
-template <int VS, int NDB>
-__device__ __forceinline__ void vt_issue(VtFrags<NDB> &f, const __bf16 *vp) {
-  const unsigned addr = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) __bf16 *)vp;
-#pragma unroll
-  for (int db = 0; db < NDB; ++db) {
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.lo[db]) : "v"(addr), "n"(db * 64));
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi[db]) : "v"(addr), "n"(db * 64 + 8 * VS * 2));
-  }
-}
-// K operands of S^T = K Q^T for 32 keys (NKS k-steps of 16 channels), same hand-issued style.
-template <int NKS>
-struct KFrags {
-  u32x4 a[NKS];
-};
-template <int NKS>
-__device__ __forceinline__ void kf_issue(KFrags<NKS> &f, const __bf16 *kp) {
-  const unsigned addr = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) __bf16 *)kp;
-#pragma unroll
-  for (int k = 0; k < NKS; ++k) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.a[k]) : "v"(addr), "n"(k * 32));
-}
-// Counted waits: LDS operations of a wave complete in order, so "at most N outstanding" means everything
-// issued before the last N has arrived.
-template <int N>
-__device__ __forceinline__ void kf_wait_n(KFrags<4> &f) {
-  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]) : "n"(N));
-}
-template <int N>
-__device__ __forceinline__ void vt_wait_n(VtFrags<4> &f) {
-  asm volatile("s_waitcnt lgkmcnt(%8)"
-               : "+v"(f.lo[0]), "+v"(f.lo[1]), "+v"(f.lo[2]), "+v"(f.lo[3]), "+v"(f.hi[0]), "+v"(f.hi[1]), "+v"(f.hi[2]),
-                 "+v"(f.hi[3])
-               : "n"(N));
-}
-__device__ __forceinline__ void kf_wait(KFrags<8> &f) {
-  asm volatile("s_waitcnt lgkmcnt(0)"
-               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.a[4]), "+v"(f.a[5]), "+v"(f.a[6]), "+v"(f.a[7]));
-}
-__device__ __forceinline__ void vt_wait(VtFrags<4> &f, VtFrags<4> &h) {
-  asm volatile("s_waitcnt lgkmcnt(0)"
-               : "+v"(f.lo[0]), "+v"(f.lo[1]), "+v"(f.lo[2]), "+v"(f.lo[3]), "+v"(f.hi[0]), "+v"(f.hi[1]), "+v"(f.hi[2]),
-                 "+v"(f.hi[3]), "+v"(h.lo[0]), "+v"(h.lo[1]), "+v"(h.lo[2]), "+v"(h.lo[3]), "+v"(h.hi[0]), "+v"(h.hi[1]),
-                 "+v"(h.hi[2]), "+v"(h.hi[3]));
-}
-
 // ---------------------------------------------------------------------------------------------------
 // The rescaling ("classic") loop over key tiles [kt0, kt1): load tile -> S^T -> online softmax with
-// running-maximum rescaling -> O^T.  Used by pf_attn_kernel and as the fallback of the pipelined kernel.
+// running-maximum rescaling -> O^T.  Used by pf_attn_kernel.
 // ---------------------------------------------------------------------------------------------------
 template <int D, int NQB>
 __device__ __forceinline__ void classic_loop(const HeadKV &H, int kt0, int kt1, const bf16x8 (&qf)[NQB][D / 16],
@@ -625,417 +512,7 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void pf_attn_kernel(AttnParams P) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Kernel 1: 64 query rows per wave, software-pipelined over 32-key half tiles.
-// ---------------------------------------------------------------------------------------------------
-// One half tile (32 keys) in two scheduling regions, each pairing 16 matrix instructions with vector work:
-//   region 1   S^T of the NEXT 32 keys (K fragments fetched from LDS during the previous call)
-//              || row maxima and the weights of the first 16 current keys; the V^T fragments of the
-//              current keys are fetched meanwhile
-//   region 2   O^T += V^T P^T for the 32 current keys || the weights of the last 16; the K fragments of the
-//              keys after next (PREFETCH) are fetched meanwhile
-// The accumulators are never rescaled here: weights are taken relative to a fixed reference maximum m_ref
-// per row, with 2^60 of headroom.  m_seen tracks the largest score met; a score beyond the headroom is
-// reported and the workgroup redoes its item with m_ref = the exact row maxima.
-template <int D, bool NEXT, bool PREFETCH>
-__device__ __forceinline__ bool pipe_half(f32x16 (&s_cur)[2], f32x16 (&s_next)[2], f32x16 (&o)[2][D / 32],
-                                          const float (&m_ref)[2], float (&m_seen)[2], float (&l_run)[2],
-                                          const bf16x8 (&qf)[2][D / 16], KFrags<D / 16> &kf, const __bf16 *sKpf,
-                                          const __bf16 *sVc, int k_lane, int v_lane, float c, float thr) {
-  constexpr int VS = D + 32, NKS = D / 16, NDB = D / 32;
-  const float mc[2] = {m_ref[0] * c, m_ref[1] * c};
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-  bf16x8 pf[2][2];                                  // [chunk][query block]: P^T operands
-  auto exp_chunk = [&](int c2) {
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      bf16x2 pk[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float p0 = fast_exp2(fmaf(s_cur[qb][8 * c2 + 2 * e], c, -mc[qb]));
-        const float p1 = fast_exp2(fmaf(s_cur[qb][8 * c2 + 2 * e + 1], c, -mc[qb]));
-        pk[e][0] = (__bf16)p0;
-        pk[e][1] = (__bf16)p1;
-        l_run[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk[e], ones, l_run[qb], false);   // sums the rounded weights
-      }
-      const bf16x4 lo = __builtin_shufflevector(pk[0], pk[1], 0, 1, 2, 3);
-      const bf16x4 hi = __builtin_shufflevector(pk[2], pk[3], 0, 1, 2, 3);
-      pf[c2][qb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    }
-  };
-
-  // ---- region 1 ----
-  if (NEXT) kf_wait(kf);
-  VtFrags<NDB> vf[2];
-  vt_issue<VS, NDB>(vf[0], &sVc[v_lane]);
-  vt_issue<VS, NDB>(vf[1], &sVc[v_lane + 16 * VS]);
-  float mx[2];
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    float a = s_cur[qb][0];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) a = fmaxf(a, s_cur[qb][i]);
-    mx[qb] = a;                                     // per-lane maximum is enough for the overflow test
-    m_seen[qb] = fmaxf(m_seen[qb], a);
-  }
-  const bool overflow = (mx[0] > m_ref[0] + thr) || (mx[1] > m_ref[1] + thr);
-  if (NEXT) {
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, kf.a[ks]);
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        if (ks == 0) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) s_next[qb][i] = 0.0f;
-        }
-        s_next[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s_next[qb], 0, 0, 0);
-      }
-    }
-  }
-  exp_chunk(0);
-
-  // ---- region 2 ----
-  vt_wait(vf[0], vf[1]);
-  if (PREFETCH) kf_issue<NKS>(kf, &sKpf[k_lane]);
-  exp_chunk(1);
-#pragma unroll
-  for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-    for (int db = 0; db < NDB; ++db) {
-      const s16x8 av = __builtin_shufflevector(vf[c2].lo[db], vf[c2].hi[db], 0, 1, 2, 3, 4, 5, 6, 7);
-      const bf16x8 a = __builtin_bit_cast(bf16x8, av);
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
-        o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[c2][qb], o[qb][db], 0, 0, 0);
-    }
-  return overflow;
-}
-
-template <int D>
-__global__ __launch_bounds__(ATT_THREADS, 1) void pf_attn_pipe_kernel(AttnParams P) {
-  constexpr int NQB = 2;
-  constexpr int BK = PF_BK;
-  constexpr int KS = D + 8, VS = D + 32;
-  constexpr int NKS = D / 16;
-
-  __shared__ __attribute__((aligned(16))) __bf16 sK[3][BK * KS];   // K of tiles kt, kt+1 (being read) and kt+2 (landing)
-  __shared__ __attribute__((aligned(16))) __bf16 sV[2][BK * VS];
-  __shared__ int32_t sFlag;
-  __shared__ int32_t sRedo;
-
-  const PfWorkItem it = P.items[blockIdx.x];
-  if (it.head < 0) return;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int l32 = lane & 31, g = lane >> 5;
-  HeadKV H;
-  bf16x8 qf[NQB][NKS];
-  attn_setup<D, NQB>(P, it, H, qf);
-  if (tid == 0) sRedo = 0;
-
-  const int k_lane = l32 * KS + 8 * g;
-  const int v_lane = (4 * g + ((lane & 15) >> 2)) * VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  const float c = P.scale_log2;
-  const float thr = ATT_PIPE_LOG2 / c;
-
-  f32x16 o[NQB][D / 32];
-  float m_ref[NQB], l_run[NQB];
-  float m_seen[NQB] = {-3.0e38f, -3.0e38f};         // largest score met per row (this lane's share of the keys)
-
-  // Attempt 0 takes the reference maxima from the item's first 32 keys.  If a later score outgrows the
-  // headroom (never seen on attention-like inputs), the pass still runs to the end to learn the exact row
-  // maxima, and attempt 1 repeats the item with those: it cannot overflow.
-  for (int attempt = 0; attempt < 2; ++attempt) {
-    float dummy[NQB];
-    attn_zero<D, NQB>(o, dummy, l_run);
-
-    // ---- prologue: K and V of the first tile, K of the second, then S^T of the first 32 keys ----
-    TilePos posK = tile_pos_init(it.kt0, H.hist_tokens, H.n_sel, H.tpf), posV = posK;
-    dma_tile<D, KS>(it.kt0, posK, H, H.k_pool, H.k_cur, sK[0], wave, lane);
-    dma_tile<D, VS>(it.kt0, posV, H, H.v_pool, H.v_cur, sV[0], wave, lane);
-    if (it.kt0 + 1 < it.kt1) {
-      tile_pos_advance(posK, H.n_sel, H.tpf);
-      dma_tile<D, KS>(it.kt0 + 1, posK, H, H.k_pool, H.k_cur, sK[1], wave, lane);
-    }
-    __syncthreads();
-    f32x16 s_a[NQB], s_b[NQB];                     // scores of the current / next 32-key half tile (roles swap)
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s_a[qb][i] = 0.0f;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      const bf16x8 a = *(const bf16x8 *)(&sK[0][k_lane + ks * 16]);
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) s_a[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s_a[qb], 0, 0, 0);
-    }
-    KFrags<NKS> kf;                                 // K fragments of the 32 keys after the current ones
-    kf_issue<NKS>(kf, &sK[0][32 * KS + k_lane]);
-    if (attempt == 0) {
-      const int valid0 = H.lkv - it.kt0 * BK;       // >= 1: the first key of a work item always exists
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        float a = -3.0e38f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (8 * (i >> 2) + 4 * g + (i & 3) < valid0) a = fmaxf(a, s_a[qb][i]);
-        m_ref[qb] = partner_max(a);
-      }
-    } else {
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) m_ref[qb] = partner_max(m_seen[qb]);
-    }
-
-    // ---- main loop.  Per 64-key tile kt: first half (keys 0-31) runs while S^T of keys 32-63 is computed,
-    // second half while S^T of the first 32 keys of tile kt+1 is computed.  K of tile kt+2 and V of tile kt+1
-    // are copied global -> LDS meanwhile, into buffers last read one tile ago. ----
-    bool overflow = false;
-    int kt = it.kt0;
-    int kb0 = 0;                                      // K buffer of the current tile: (kt - kt0) % 3
-    for (; kt + 1 < it.kt1; ++kt) {                   // every tile but the last: no ragged tail, a next tile exists
-      const int cb = (kt - it.kt0) & 1;               // V buffer of the current tile
-      const int kb1 = kb0 == 2 ? 0 : kb0 + 1, kb2 = kb1 == 2 ? 0 : kb1 + 1;
-      if (kt + 2 < it.kt1) {
-        tile_pos_advance(posK, H.n_sel, H.tpf);
-        dma_tile<D, KS>(kt + 2, posK, H, H.k_pool, H.k_cur, sK[kb2], wave, lane);
-      }
-      tile_pos_advance(posV, H.n_sel, H.tpf);
-      dma_tile<D, VS>(kt + 1, posV, H, H.v_pool, H.v_cur, sV[cb ^ 1], wave, lane);
-      __builtin_amdgcn_sched_barrier(0);              // the two halves are scheduled on their own: short live ranges
-      overflow |= pipe_half<D, true, true>(s_a, s_b, o, m_ref, m_seen, l_run, qf, kf, &sK[kb1][0], &sV[cb][0], k_lane, v_lane, c, thr);
-      __builtin_amdgcn_sched_barrier(0);
-      overflow |= pipe_half<D, true, true>(s_b, s_a, o, m_ref, m_seen, l_run, qf, kf, &sK[kb1][32 * KS], &sV[cb][32 * VS], k_lane, v_lane, c, thr);
-      __builtin_amdgcn_sched_barrier(0);
-      __syncthreads();                                // tiles kt+2 (K) and kt+1 (V) have landed; tile kt is dead
-      kb0 = kb1;
-    }
-    {                                                 // last tile: ragged tail possible, nothing follows
-      const int cb = (kt - it.kt0) & 1;
-      const int kb1 = kb0 == 2 ? 0 : kb0 + 1;
-      const int valid = H.lkv - kt * BK;
-      if (valid < BK) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          if (8 * (i >> 2) + 4 * g + (i & 3) >= valid) {
-#pragma unroll
-            for (int qb = 0; qb < NQB; ++qb) s_a[qb][i] = -INFINITY;
-          }
-        }
-      }
-      overflow |= pipe_half<D, true, false>(s_a, s_b, o, m_ref, m_seen, l_run, qf, kf, &sK[kb1][0], &sV[cb][0], k_lane, v_lane, c, thr);
-      if (valid < BK) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          if (32 + 8 * (i >> 2) + 4 * g + (i & 3) >= valid) {
-#pragma unroll
-            for (int qb = 0; qb < NQB; ++qb) s_b[qb][i] = -INFINITY;
-          }
-        }
-      }
-      overflow |= pipe_half<D, false, false>(s_b, s_a, o, m_ref, m_seen, l_run, qf, kf, &sK[kb1][0], &sV[cb][32 * VS], k_lane, v_lane, c, thr);
-    }
-    if (attempt == 1) break;
-    if (__builtin_amdgcn_ballot_w64(overflow) != 0 && lane == 0) sRedo = 1;
-    __syncthreads();
-    if (!sRedo) break;                                // uniform across the workgroup: read after the barrier
-  }
-  attn_epilogue<D, NQB>(P, it, o, m_ref, l_run, (float *)&sK[0][0], &sFlag);
-}
-
-// ---------------------------------------------------------------------------------------------------
-// Kernel 1 (default for head_dim 128): 8 waves x 32 query rows (BQ = 256), one workgroup per CU, K/V tiles in a
-// 4-stage LDS ring filled by direct global -> LDS copies issued three tiles ahead.  The copies use no
-// registers and no LDS-write instructions, are waited for with a counted s_waitcnt (the copies of the next
-// tiles stay in flight), and each tile is fetched once for 256 query rows.  LDS fragment reads are issued by
-// hand (the compiler would wait for ALL outstanding copies before any LDS read it knows about), a few
-// fragments ahead of the MFMAs that consume them.  Softmax as in the rescaling loop.
-// ---------------------------------------------------------------------------------------------------
-constexpr int RING_WAVES = 8;
-constexpr int RING_STAGES = 4;
-
-template <int D>
-__global__ __launch_bounds__(RING_WAVES * 64, 2) void pf_attn_ring_kernel(AttnParams P) {
-  static_assert(D == 128, "direct global -> LDS rows are 64 lanes x 4 bytes");
-  constexpr int BK = PF_BK;
-  constexpr int KS = D + 8, VS = D + 32;
-  constexpr int NKS = D / 16, NDB = D / 32;
-  constexpr int DMA_PER_TILE = 2 * (BK / RING_WAVES);          // copy instructions per wave per tile (K + V)
-  static_assert(2 * DMA_PER_TILE <= 63, "vmcnt field");
-
-  __shared__ __attribute__((aligned(16))) __bf16 sK[RING_STAGES][BK * KS];
-  __shared__ __attribute__((aligned(16))) __bf16 sV[RING_STAGES][BK * VS];
-  __shared__ int32_t sFlag;
-
-  const PfWorkItem it = P.items[blockIdx.x];
-  if (it.head < 0) return;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int l32 = lane & 31, g = lane >> 5;
-  HeadKV H;
-  bf16x8 qf[1][NKS];
-  attn_setup<D, 1>(P, it, H, qf);
-  f32x16 o[1][NDB];
-  float m_run[1], l_run[1];
-  attn_zero<D, 1>(o, m_run, l_run);
-  const int k_lane = l32 * KS + 8 * g;
-  const int v_lane = (4 * g + ((lane & 15) >> 2)) * VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  const float c = P.scale_log2;
-  const float thr = ATT_LAZY_LOG2 / c;
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-
-  // Q^T has arrived before the first copy is issued: a wait for it later would also wait for every copy
-  // issued in between (vector-memory operations complete in order)
-#pragma unroll
-  for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[0][ks]));
-
-  // ---- prologue: the first three tiles start travelling ----
-  TilePos pos = tile_pos_init(it.kt0, H.hist_tokens, H.n_sel, H.tpf);
-#pragma unroll
-  for (int a = 0; a < RING_STAGES - 1; ++a) {
-    if (it.kt0 + a < it.kt1) {
-      if (a > 0) tile_pos_advance(pos, H.n_sel, H.tpf);
-      dma_tile<D, KS, RING_WAVES>(it.kt0 + a, pos, H, H.k_pool, H.k_cur, sK[a], wave, lane);
-      dma_tile<D, VS, RING_WAVES>(it.kt0 + a, pos, H, H.v_pool, H.v_cur, sV[a], wave, lane);
-    }
-  }
-
-  int st = 0;                                                  // ring stage of the current tile
-  for (int kt = it.kt0; kt < it.kt1; ++kt) {
-    // this wave's copies of tile kt have landed once at most the copies of the tiles after it are outstanding
-    const int ahead = pf_min(it.kt1 - 1 - kt, RING_STAGES - 2);
-    if (ahead >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (((2 * DMA_PER_TILE) & 15)) | (((2 * DMA_PER_TILE) >> 4) << 14));
-    else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | ((DMA_PER_TILE & 15)) | ((DMA_PER_TILE >> 4) << 14));
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
-    __builtin_amdgcn_s_barrier();                              // everyone's rows of tile kt landed; tile kt-1 is dead
-    // the stage tile kt-1 lived in is refilled with tile kt+3, two rows at a time between the MFMA groups below
-    const bool refill = kt + RING_STAGES - 1 < it.kt1;
-    const int sn = (st + RING_STAGES - 1) & (RING_STAGES - 1);
-    TileSrc src;
-    if (refill) {
-      tile_pos_advance(pos, H.n_sel, H.tpf);
-      src = tile_src(kt + RING_STAGES - 1, pos, H, D);
-    }
-    constexpr int RPW = BK / RING_WAVES;                        // rows per wave and tensor
-    auto copy_k = [&](int r2) {
-      if (!refill) return;
-      dma_row<D, KS, false>(src, H, wave * RPW + 2 * r2, sK[sn], lane);
-      dma_row<D, KS, false>(src, H, wave * RPW + 2 * r2 + 1, sK[sn], lane);
-    };
-    auto copy_v = [&](int r2) {
-      if (!refill) return;
-      dma_row<D, VS, true>(src, H, wave * RPW + 2 * r2, sV[sn], lane);
-      dma_row<D, VS, true>(src, H, wave * RPW + 2 * r2 + 1, sV[sn], lane);
-    };
-    const __bf16 *tK = &sK[st][k_lane];
-    const __bf16 *tV = &sV[st][v_lane];
-
-    // ---- S^T = K Q^T: four groups of four K fragments, two groups in flight ----
-    f32x16 s[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[kb][i] = 0.0f;
-    KFrags<4> ka, kb_;
-    VtFrags<NDB> va, vb;
-    kf_issue<4>(ka, tK);
-    kf_issue<4>(kb_, tK + 4 * 16);
-    kf_wait_n<4>(ka);
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka.a[k]), qf[0][k], s[0], 0, 0, 0);
-    copy_k(0);
-    kf_issue<4>(ka, tK + 32 * KS);
-    kf_wait_n<4>(kb_);
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb_.a[k]), qf[0][4 + k], s[0], 0, 0, 0);
-    copy_k(1);
-    kf_issue<4>(kb_, tK + 32 * KS + 4 * 16);
-    kf_wait_n<4>(ka);
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka.a[k]), qf[0][k], s[1], 0, 0, 0);
-    copy_k(2);
-    vt_issue<VS, NDB>(va, tV);
-    kf_wait_n<8>(kb_);
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb_.a[k]), qf[0][4 + k], s[1], 0, 0, 0);
-    copy_k(3);
-    vt_issue<VS, NDB>(vb, tV + 16 * VS);
-
-    const int valid = H.lkv - kt * BK;                          // ragged tail: only the head's last tile
-    if (valid < BK) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3) >= valid) s[kb][i] = -INFINITY;
-    }
-
-    // ---- online softmax with deferred rescaling (see the rescaling loop) ----
-    float mx = s[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
-    mx = partner_max(mx);
-    if (__builtin_amdgcn_ballot_w64(mx > m_run[0] + thr) != 0) {
-      const float m_new = fmaxf(m_run[0], mx);
-      const float alpha = fast_exp2((m_run[0] - m_new) * c);
-      m_run[0] = m_new;
-      l_run[0] *= alpha;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[0][db][i] *= alpha;
-    }
-    const float mc = m_run[0] * c;
-    bf16x8 pf[4];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; i += 2) {
-        bf16x2 pk;
-        pk[0] = (__bf16)fast_exp2(fmaf(s[kb][i], c, -mc));
-        pk[1] = (__bf16)fast_exp2(fmaf(s[kb][i + 1], c, -mc));
-        l_run[0] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run[0], false);
-        pf[kb * 2 + (i >> 3)][i & 7] = pk[0];
-        pf[kb * 2 + (i >> 3)][(i & 7) + 1] = pk[1];
-      }
-
-    // ---- O^T += V^T P^T: four 16-key chunks, two chunks of V^T fragments in flight ----
-    auto pv = [&](VtFrags<NDB> &vf, int c4) {
-#pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-        const s16x8 av = __builtin_shufflevector(vf.lo[db], vf.hi[db], 0, 1, 2, 3, 4, 5, 6, 7);
-        o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pf[c4], o[0][db], 0, 0, 0);
-      }
-    };
-    vt_wait_n<8>(va);
-    pv(va, 0);
-    copy_v(0);
-    vt_issue<VS, NDB>(va, tV + 32 * VS);
-    vt_wait_n<8>(vb);
-    pv(vb, 1);
-    copy_v(1);
-    vt_issue<VS, NDB>(vb, tV + 48 * VS);
-    vt_wait_n<8>(va);
-    pv(va, 2);
-    copy_v(2);
-    vt_wait_n<0>(vb);
-    pv(vb, 3);
-    copy_v(3);
-    st = (st + 1) & (RING_STAGES - 1);
-  }
-  __syncthreads();                                             // all LDS reads done before the stages are reused
-  attn_epilogue<D, 1, RING_WAVES>(P, it, o, m_run, l_run, (float *)&sK[0][0], &sFlag);
-}
-
-// ---------------------------------------------------------------------------------------------------
-// Kernel 3: 8 waves x 32 query rows (BQ = 256) in two groups of four that alternate between a matrix phase
+// Kernel 1 (default for head_dim 128): 8 waves x 32 query rows (BQ = 256) in two groups of four that alternate between a matrix phase
 // and a vector phase.  Waves w and w+4 share a SIMD; group 1 runs one phase behind group 0, so while one
 // wave of a SIMD issues the 32 MFMAs of a tile (O^T += V^T P^T of the previous tile, then S^T = K Q^T of
 // the current one) the other computes its softmax on the vector ALU.  A workgroup barrier ends every phase
@@ -1045,7 +522,8 @@ __global__ __launch_bounds__(RING_WAVES * 64, 2) void pf_attn_ring_kernel(AttnPa
 //                wait for this wave's copies of tile u+1
 //   phase V(u)   scores of tile u -> weights (masking of the ragged tail, lazy rescaling as in the
 //                rescaling loop); requests the first V^T fragments of tile u for the next matrix phase
-// K/V tiles travel global -> LDS two tiles ahead into a 4-stage ring with 16-byte copies: one instruction
+// K/V tiles travel global -> LDS three tiles ahead (K ring of 4 stages, V ring of 5: V of a tile is read one
+// phase after its K) with 16-byte copies: one instruction
 // moves four 256-byte rows (lane i -> bytes 16*i of the 1 KB destination), a quarter of the instructions the
 // 4-byte form needs, and the cost of these copies is per instruction.  The destination of such a copy is
 // contiguous, so rows cannot be padded; bank conflicts are avoided by permuting the 16-byte chunks of a row
@@ -1397,17 +875,13 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
 
 static int launch_attn(const AttnParams &P, int head_dim, int variant, int n_blocks, hipStream_t stream) {
   if (head_dim == 128 && variant == 1)
-    hipLaunchKernelGGL((pf_attn_ring_kernel<128>), dim3(n_blocks), dim3(RING_WAVES * 64), 0, stream, P);
-  else if (head_dim == 128 && variant == 3)
     hipLaunchKernelGGL((pf_attn_pp_kernel<128>), dim3(n_blocks), dim3(PP_WAVES * 64), 0, stream, P);
-  else if (head_dim == 128 && variant == 2)
-    hipLaunchKernelGGL((pf_attn_pipe_kernel<128>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
   else if (head_dim == 128 && variant == 0)
     hipLaunchKernelGGL((pf_attn_kernel<128>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
   else if (head_dim == 64 && variant == 0)
     hipLaunchKernelGGL((pf_attn_kernel<64>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
   else
-    return PF_ERR_UNSUPPORTED;                      // kernels 1 and 2 exist for head_dim 128 only
+    return PF_ERR_UNSUPPORTED;                      // kernel 1 exists for head_dim 128 only
   return hipGetLastError() == hipSuccess ? PF_OK : PF_ERR_HIP;
 }
 

@@ -49,7 +49,7 @@ int pf_resolve_variant(int head_dim) {
   const char *e = getenv("PF_ATTN_VARIANT");
   int v = e ? atoi(e) : PF_DEFAULT_VARIANT;
   if (v < 0 || v >= PF_NUM_VARIANTS) v = PF_DEFAULT_VARIANT;
-  return head_dim == 128 ? v : 0;                   // kernels 1 and 2 exist for head_dim 128 only
+  return head_dim == 128 ? v : 0;                   // kernel 1 exists for head_dim 128 only
 }
 
 void pf_host_plan(const pf_pool *pool, int T, int q_tokens, int variant, int seg_tiles,

@@ -12,7 +12,7 @@ import gpu_common as G
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=[0, 1, 2, 3], ids=["w4x32", "ring8x32", "pipe4x64", "pp8x32"])
+@pytest.fixture(params=[0, 1], ids=["w4x32", "pp8x32"])
 def variant(request):
     old = os.environ.get("PF_ATTN_VARIANT")
     os.environ["PF_ATTN_VARIANT"] = str(request.param)
@@ -51,9 +51,8 @@ def test_peaked_logits(variant):
 
 
 def test_scores_far_above_the_first_keys(variant):
-    """Queries x64: later keys beat the first 32 keys of a work item by far more than 2^60 in the exponent, which
-    makes the pipelined kernel give up its fixed reference maximum and redo the item with the exact row maxima
-    (the other kernel just rescales)."""
+    """Queries x64: later keys beat the first keys of a work item by hundreds of units in the exponent, so the
+    reference maximum has to move (and the accumulators be rescaled) many times."""
     a, r = G.run_case(_mixed(12), 48, 128, [3, 3, 3, 3], 200, seed=15, q_gain=64.0, seg_tiles=16, label="huge")
     print("huge logits max-abs %.2e rel %.2e" % (a, r))
 
