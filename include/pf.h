@@ -117,7 +117,7 @@ typedef struct pf_pool {
  */
 typedef struct pf_index {
   int32_t max_sel;                /* row length of sel_frames / sel_slots */
-  int32_t seg_tiles;              /* tuning: key tiles per work item, 0 = library default */
+  int32_t seg_tiles;              /* tuning: key tiles per work item, 0 = chosen by the library per launch */
   int32_t *sel_count;             /* dev [n_heads] */
   int32_t *sel_frames;            /* dev [n_heads][max_sel], unused entries -1 */
   int32_t *sel_slots;             /* dev [n_heads][max_sel], global pool slots, unused -1 */
@@ -130,7 +130,7 @@ typedef struct pf_index {
   int32_t n_blocks;               /* workgroups of the attention launch */
   int32_t n_partials;             /* partial-result slots the launch uses */
   int32_t variant;                /* kernel variant the plan was built for */
-  int32_t reserved;
+  int32_t reserved;               /* segment length the library chose (0 when the caller fixed it); start at 0 */
 } pf_index;
 
 /* ---- sizes (host only, no device access) -------------------------------- */

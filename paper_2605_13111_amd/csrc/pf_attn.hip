@@ -22,6 +22,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // 16-byte register quad
@@ -313,38 +314,59 @@ __device__ __forceinline__ void classic_loop(const HeadKV &H, int kt0, int kt1, 
 // ---------------------------------------------------------------------------------------------------
 // Final normalisation and store.  Unsplit heads write bf16 output directly; split heads park the
 // unnormalised partial (O, m, l) and the last segment to arrive merges all partials of its (head, query tile).
-// sScratch: at least 2*BQ floats of LDS that no wave reads any more (every wave passed the loop's last barrier).
+// The accumulators hold O^T (one query column per lane); they go through LDS once so that every global
+// access of the epilogue is a full row segment: 16 bytes per lane, consecutive lanes consecutive addresses.
+// sStage: attn_stage_floats(BQ, D) floats of LDS that no wave reads any more (all passed the loop's last barrier).
 // ---------------------------------------------------------------------------------------------------
+constexpr int attn_stage_floats(int bq, int d) { return bq * (d + 4) + 2 * bq; }
+
+// 16-byte device-scope store: written through to the memory all dies share (see st_dev2).
+__device__ __forceinline__ void st_dev4(float *p, f32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+}
+
 template <int D, int NQB, int NWAVES = ATT_WAVES>
 __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkItem &it, f32x16 (&o)[NQB][D / 32],
-                                              float (&m_run)[NQB], float (&l_run)[NQB], float *sScratch, int32_t *sFlagp) {
+                                              float (&m_run)[NQB], float (&l_run)[NQB], float *sStage, int32_t *sFlagp) {
   constexpr int BQ = NWAVES * 32 * NQB;
   constexpr int NT = NWAVES * 64;
   constexpr int NDB = D / 32;
+  constexpr int LD = D + 4;                        // row stride of the staged tile: 16-byte writes of 16 rows hit all banks
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int h = it.head;
   const float c = P.scale_log2;
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) l_run[qb] = partner_sum(l_run[qb]);
+  float *sO = sStage;                              // [BQ][LD]
+  float *sM = sStage + BQ * LD, *sL = sM + BQ;     // [BQ] each
 
+  // ---- accumulators -> LDS rows ----
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int lrow_q = (wave * NQB + qb) * 32 + l32;
+    const float lsum = partner_sum(l_run[qb]);
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4)
+        *(float4 *)(sO + lrow_q * LD + db * 32 + 8 * i4 + 4 * g) =
+            make_float4(o[qb][db][i4 * 4], o[qb][db][i4 * 4 + 1], o[qb][db][i4 * 4 + 2], o[qb][db][i4 * 4 + 3]);
+    if (g == 0) { sM[lrow_q] = m_run[qb]; sL[lrow_q] = lsum; }
+  }
+  __syncthreads();
+
+  __bf16 *oh = P.out + (size_t)h * P.q_tokens * D;
   if (it.nseg == 1) {
-    __bf16 *oh = P.out + (size_t)h * P.q_tokens * D;
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      const int row = it.q0 + (wave * NQB + qb) * 32 + l32;
+    for (int e = tid; e < BQ * (D / 8); e += NT) {
+      const int r = e / (D / 8), d0 = (e % (D / 8)) * 8;
+      const int row = it.q0 + r;
       if (row >= P.q_tokens) continue;
-      const float inv = 1.0f / l_run[qb];
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          bf16x4 w;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[qb][db][i4 * 4 + e] * inv);
-          *(bf16x4 *)(oh + (size_t)row * D + db * 32 + 8 * i4 + 4 * g) = w;
-        }
+      const float inv = 1.0f / sL[r];
+      const float4 a = *(const float4 *)(sO + r * LD + d0), b = *(const float4 *)(sO + r * LD + d0 + 4);
+      bf16x8 w;
+      w[0] = (__bf16)(a.x * inv); w[1] = (__bf16)(a.y * inv); w[2] = (__bf16)(a.z * inv); w[3] = (__bf16)(a.w * inv);
+      w[4] = (__bf16)(b.x * inv); w[5] = (__bf16)(b.y * inv); w[6] = (__bf16)(b.z * inv); w[7] = (__bf16)(b.w * inv);
+      *(bf16x8 *)(oh + (size_t)row * D + d0) = w;
     }
     return;
   }
@@ -353,20 +375,12 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
   const size_t part_floats = (size_t)BQ * (D + 2);
   {
     float *po = P.workspace + (size_t)(it.part0 + it.seg * P.n_qt) * part_floats;
-    float *pm = po + (size_t)BQ * D, *pl = pm + BQ;
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      const int lrow_q = (wave * NQB + qb) * 32 + l32;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          float *dst = po + (size_t)lrow_q * D + db * 32 + 8 * i4 + 4 * g;
-          st_dev2(dst, o[qb][db][i4 * 4], o[qb][db][i4 * 4 + 1]);
-          st_dev2(dst + 2, o[qb][db][i4 * 4 + 2], o[qb][db][i4 * 4 + 3]);
-        }
-      if (g == 0) { st_dev1(pm + lrow_q, m_run[qb]); st_dev1(pl + lrow_q, l_run[qb]); }
+    float *pm = po + (size_t)BQ * D;                // m[BQ] then l[BQ]
+    for (int e = tid; e < BQ * (D / 4); e += NT) {
+      const int r = e / (D / 4), d0 = (e % (D / 4)) * 4;
+      st_dev4(po + (size_t)r * D + d0, *(const f32x4 *)(sO + r * LD + d0));
     }
+    for (int e = tid; e < 2 * BQ; e += NT) st_dev1(pm + e, sM[e]);      // sM and sL are adjacent
   }
   __builtin_amdgcn_s_waitcnt(0);             // this wave's partial stores have completed
   __syncthreads();
@@ -378,11 +392,14 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
   __syncthreads();
   if (!*sFlagp) return;
 
-  // ---- merge.  Phase A: per query row, the maximum M over the segments' reference maxima and the total
-  // denominator L = sum_s 2^((m_s-M)c) l_s.  Phase B: out = sum_s 2^((m_s-M)c) O_s / L.  Both phases keep
-  // many independent loads in flight: the merge is pure memory latency otherwise. ----
-  float *sM = sScratch;
-  float *sInvL = sM + BQ;
+  // ---- merge.  The other segments' stores went through to memory before their arrival was counted; what
+  // this die's L2 may still hold of these addresses is older (the workspace is reused by every launch), so
+  // the L2 copies are dropped first (acquire at device scope: an invalidate, no write-back) and the partials
+  // are then read with ordinary wide loads.
+  // Phase A: per query row, the maximum M over the segments' reference maxima and the total denominator
+  // L = sum_s 2^((m_s-M)c) l_s.  Phase B: out = sum_s 2^((m_s-M)c) O_s / L. ----
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  float *sInvL = sL;
   const float *base = P.workspace + (size_t)it.part0 * part_floats;
   const size_t seg_stride = (size_t)P.n_qt * part_floats;
   const int nseg = it.nseg;
@@ -390,39 +407,38 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
     const float *pm = base + (size_t)BQ * D + r;
     float mmax = -3.0e38f;
 #pragma unroll 8
-    for (int sgi = 0; sgi < nseg; ++sgi) mmax = fmaxf(mmax, ld_dev1(pm + sgi * seg_stride));
+    for (int sgi = 0; sgi < nseg; ++sgi) mmax = fmaxf(mmax, pm[sgi * seg_stride]);
     float lsum = 0.0f;
 #pragma unroll 8
-    for (int sgi = 0; sgi < nseg; ++sgi)
-      lsum += fast_exp2((ld_dev1(pm + sgi * seg_stride) - mmax) * c) * ld_dev1(pm + sgi * seg_stride + BQ);
+    for (int sgi = 0; sgi < nseg; ++sgi) lsum += fast_exp2((pm[sgi * seg_stride] - mmax) * c) * pm[sgi * seg_stride + BQ];
     sM[r] = mmax;
     sInvL[r] = 1.0f / lsum;
   }
   __syncthreads();
-  __bf16 *oh = P.out + (size_t)h * P.q_tokens * D;
-  constexpr int EG = 4;                                        // output quads per thread in flight
-  static_assert((BQ * (D / 4)) % (NT * EG) == 0, "merge tiling");
-  for (int e0 = tid; e0 < BQ * (D / 4); e0 += NT * EG) {
-    int r[EG], dc[EG];
+  constexpr int EG = 4;                                        // 8-channel output groups per thread in flight
+  static_assert((BQ * (D / 8)) % (NT * EG) == 0, "merge tiling");
+  for (int e0 = tid; e0 < BQ * (D / 8); e0 += NT * EG) {
+    int r[EG], d0[EG];
     float mrow[EG];
-    float4 acc[EG];
+    float4 acc[EG][2];
 #pragma unroll
     for (int k = 0; k < EG; ++k) {
       const int e = e0 + k * NT;
-      r[k] = e / (D / 4);
-      dc[k] = (e % (D / 4)) * 4;
+      r[k] = e / (D / 8);
+      d0[k] = (e % (D / 8)) * 8;
       mrow[k] = sM[r[k]];
-      acc[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      acc[k][0] = acc[k][1] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
-#pragma unroll 4
+#pragma unroll 2
     for (int sgi = 0; sgi < nseg; ++sgi) {
       const float *ps = base + sgi * seg_stride;
 #pragma unroll
       for (int k = 0; k < EG; ++k) {
-        const float w = fast_exp2((ld_dev1(ps + (size_t)BQ * D + r[k]) - mrow[k]) * c);
-        const float2 va = ld_dev2(ps + (size_t)r[k] * D + dc[k]);
-        const float2 vb = ld_dev2(ps + (size_t)r[k] * D + dc[k] + 2);
-        acc[k].x += w * va.x; acc[k].y += w * va.y; acc[k].z += w * vb.x; acc[k].w += w * vb.y;
+        const float w = fast_exp2((ps[(size_t)BQ * D + r[k]] - mrow[k]) * c);
+        const float4 va = *(const float4 *)(ps + (size_t)r[k] * D + d0[k]);
+        const float4 vb = *(const float4 *)(ps + (size_t)r[k] * D + d0[k] + 4);
+        acc[k][0].x += w * va.x; acc[k][0].y += w * va.y; acc[k][0].z += w * va.z; acc[k][0].w += w * va.w;
+        acc[k][1].x += w * vb.x; acc[k][1].y += w * vb.y; acc[k][1].z += w * vb.z; acc[k][1].w += w * vb.w;
       }
     }
 #pragma unroll
@@ -430,10 +446,12 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
       const int row = it.q0 + r[k];
       if (row >= P.q_tokens) continue;
       const float inv = sInvL[r[k]];
-      bf16x4 w4;
-      w4[0] = (__bf16)(acc[k].x * inv); w4[1] = (__bf16)(acc[k].y * inv);
-      w4[2] = (__bf16)(acc[k].z * inv); w4[3] = (__bf16)(acc[k].w * inv);
-      *(bf16x4 *)(oh + (size_t)row * D + dc[k]) = w4;
+      bf16x8 w;
+      w[0] = (__bf16)(acc[k][0].x * inv); w[1] = (__bf16)(acc[k][0].y * inv);
+      w[2] = (__bf16)(acc[k][0].z * inv); w[3] = (__bf16)(acc[k][0].w * inv);
+      w[4] = (__bf16)(acc[k][1].x * inv); w[5] = (__bf16)(acc[k][1].y * inv);
+      w[6] = (__bf16)(acc[k][1].z * inv); w[7] = (__bf16)(acc[k][1].w * inv);
+      *(bf16x8 *)(oh + (size_t)row * D + d0[k]) = w;
     }
   }
 }
@@ -503,12 +521,14 @@ __device__ __forceinline__ void attn_item_classic(const AttnParams &P, const PfW
 
 template <int D>
 __global__ __launch_bounds__(ATT_THREADS, 2) void pf_attn_kernel(AttnParams P) {
-  __shared__ __attribute__((aligned(16))) __bf16 sK[2][PF_BK * (D + 8)];
-  __shared__ __attribute__((aligned(16))) __bf16 sV[2][PF_BK * (D + 32)];
+  // two K and two V tile buffers; the epilogue reuses the same memory to stage the output rows
+  constexpr int K_BYTES = 2 * PF_BK * (D + 8) * 2, V_BYTES = 2 * PF_BK * (D + 32) * 2;
+  constexpr int STAGE_BYTES = attn_stage_floats(ATT_WAVES * 32, D) * 4;
+  __shared__ __attribute__((aligned(16))) char smem[K_BYTES + V_BYTES > STAGE_BYTES ? K_BYTES + V_BYTES : STAGE_BYTES];
   __shared__ int32_t sFlag;
   const PfWorkItem it = P.items[blockIdx.x];
   if (it.head < 0) return;
-  attn_item_classic<D, 1>(P, it, sK, sV, &sFlag);
+  attn_item_classic<D, 1>(P, it, (__bf16 (*)[PF_BK * (D + 8)])smem, (__bf16 (*)[PF_BK * (D + 32)])(smem + K_BYTES), &sFlag);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -617,9 +637,12 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   typedef const __attribute__((address_space(1))) void *gptr_t;
   typedef __attribute__((address_space(3))) void *lptr_t;
 
-  __shared__ __attribute__((aligned(1024))) char sK[PP_KSTAGES][PP_TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sV[PP_VSTAGES][PP_TILE_BYTES];
+  // K ring, then V ring; the epilogue reuses the same memory to stage the output rows
+  static_assert((PP_KSTAGES + PP_VSTAGES) * PP_TILE_BYTES >= attn_stage_floats(PP_WAVES * 32, D) * 4, "output staging fits");
+  __shared__ __attribute__((aligned(1024))) char smem[(PP_KSTAGES + PP_VSTAGES) * PP_TILE_BYTES];
   __shared__ int32_t sFlag;
+  char (*sK)[PP_TILE_BYTES] = (char (*)[PP_TILE_BYTES])smem;
+  char (*sV)[PP_TILE_BYTES] = sK + PP_KSTAGES;
 
   const PfWorkItem it = P.items[blockIdx.x];
   if (it.head < 0) return;

@@ -1,5 +1,6 @@
 // Frame-index build: per-head frame selection (Sec. 4.2), boundary indices of the flattened ragged
 // history (Sec. 4.3) and the launch plan of the attention kernel.  One small launch per layer.
+#include <stdlib.h>
 #include "pf_internal.h"
 
 constexpr int INDEX_THREADS = 256;
@@ -203,7 +204,17 @@ extern "C" int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens
   if (index->seg_tiles < 0) return PF_ERR_INVALID_ARG;
 
   const int variant = pf_resolve_variant(pool->head_dim);
-  const int seg_tiles = pf_resolve_seg_tiles(index->seg_tiles);
+  // segment length: the caller's, else the PF_SEG_TILES override, else chosen for this launch (and kept while
+  // the history length, the query count and the kernel stay the same)
+  int seg_tiles;
+  if (index->seg_tiles > 0 || getenv("PF_SEG_TILES")) {
+    seg_tiles = pf_resolve_seg_tiles(index->seg_tiles);
+  } else if (index->reserved >= PF_MIN_SEG_TILES && index->T_built == pool->T_host && index->q_tokens == q_tokens &&
+             index->variant == variant) {
+    seg_tiles = index->reserved;
+  } else {
+    seg_tiles = pf_auto_seg_tiles(pool, pool->T_host, q_tokens, variant);
+  }
   int n_teams, n_blocks, n_partials, max_sel_needed;
   pf_host_plan(pool, pool->T_host, q_tokens, variant, seg_tiles, &n_teams, &n_blocks, &n_partials, &max_sel_needed);
   if (max_sel_needed > index->max_sel) return PF_ERR_CAPACITY;
@@ -246,5 +257,6 @@ extern "C" int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens
   index->n_blocks = n_blocks;
   index->n_partials = n_partials;
   index->variant = variant;
+  index->reserved = (index->seg_tiles > 0 || getenv("PF_SEG_TILES")) ? 0 : seg_tiles;
   return PF_OK;
 }

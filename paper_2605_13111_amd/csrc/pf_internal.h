@@ -136,6 +136,8 @@ PF_HD size_t pf_partial_bytes(int bq, int head_dim) { return (size_t)bq * (head_
 int pf_validate_pool(const pf_pool *pool);                 // PF_OK or error
 int pf_resolve_seg_tiles(int seg_tiles);                   // 0 -> default, else clamped to the minimum
 int pf_resolve_variant(int head_dim);                      // kernel variant in use
+// Segment length that a host replay of the launch schedule finds best for this history length.
+int pf_auto_seg_tiles(const pf_pool *pool, int T, int q_tokens, int variant);
 // Host plan for the pool's current T: per-launch block count and partial count.
 void pf_host_plan(const pf_pool *pool, int T, int q_tokens, int variant, int seg_tiles,
                   int *n_teams, int *n_blocks, int *n_partials, int *max_sel_needed);
