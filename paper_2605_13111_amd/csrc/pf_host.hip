@@ -58,7 +58,7 @@ int pf_resolve_seg_tiles(int seg_tiles) {
 // to be parked and merged) and keeping the shortest finish.
 static const int kSegCandidates[] = {48, 56, 64, 72, 80, 96, 112, 128, 144, 160, 176, 192, 224, 256, 320, 384};
 constexpr int PF_AUTO_MIN_SEG = 48;                 // smallest candidate: bounds the partial-result workspace
-constexpr double PF_BLOCK_COST = 3.0;               // set-up + first fetch + store, in key-tile times
+constexpr double PF_BLOCK_COST = 8.0;               // set-up + first fetch + store, in key-tile times (fitted to timings)
 constexpr double PF_SPLIT_COST = 2.0;               // parking / merging a partial result
 
 static double model_finish(const std::vector<int> &n_kvt, const std::vector<int> &order, int n_qt, int seg_tiles,
