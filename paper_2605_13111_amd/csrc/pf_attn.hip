@@ -459,12 +459,10 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
 // ---------------------------------------------------------------------------------------------------
 // Common set-up of a workgroup: its work item, the head's key layout, its Q^T fragments.
 // ---------------------------------------------------------------------------------------------------
-template <int D, int NQB>
-__device__ __forceinline__ void attn_setup(const AttnParams &P, const PfWorkItem &it, HeadKV &H, bf16x8 (&qf)[NQB][D / 16]) {
+template <int D>
+__device__ __forceinline__ void attn_setup_head(const AttnParams &P, const PfWorkItem &it, HeadKV &H) {
   constexpr int CPR = D / 8;
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, g = lane >> 5;
   const int h = it.head;
   H.n_sel = P.sel_count[h];
   H.tpf = P.tpf;
@@ -478,14 +476,24 @@ __device__ __forceinline__ void attn_setup(const AttnParams &P, const PfWorkItem
   H.lrow = tid / CPR;
   H.lchunk = tid % CPR;
   H.thread_off = (unsigned)((H.lrow * D + H.lchunk * 8) * 2);
-  // Q^T fragments: lane (l32, g) holds, for its query row, d = 16*ks + 8*g .. +7
-  const __bf16 *qh = P.q + (size_t)h * P.q_tokens * D;
+}
+// Q^T fragments: lane (l32, g) holds, for its query row, d = 16*ks + 8*g .. +7
+template <int D, int NQB>
+__device__ __forceinline__ void attn_load_q(const AttnParams &P, const PfWorkItem &it, bf16x8 (&qf)[NQB][D / 16]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const __bf16 *qh = P.q + (size_t)it.head * P.q_tokens * D;
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const int row = pf_min(it.q0 + (wave * NQB + qb) * 32 + l32, P.q_tokens - 1);
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) qf[qb][ks] = *(const bf16x8 *)(qh + (size_t)row * D + ks * 16 + 8 * g);
   }
+}
+template <int D, int NQB>
+__device__ __forceinline__ void attn_setup(const AttnParams &P, const PfWorkItem &it, HeadKV &H, bf16x8 (&qf)[NQB][D / 16]) {
+  attn_setup_head<D>(P, it, H);
+  attn_load_q<D, NQB>(P, it, qf);
 }
 
 template <int D, int NQB>
@@ -652,8 +660,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   const int grp = wave >> 2;
   const int l32 = lane & 31, g = lane >> 5;
   HeadKV H;
-  bf16x8 qf[1][NKS];
-  attn_setup<D, 1>(P, it, H, qf);
+  attn_setup_head<D>(P, it, H);
   f32x16 o[1][NDB];
   float m_run[1], l_run[1];
   attn_zero<D, 1>(o, m_run, l_run);
@@ -678,11 +685,6 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   // per-lane source offsets of this wave's first 4-row copy group; the second group's (rows + 4) differ in
   // one bit for K and not at all for V
   const unsigned vofK = pp_group_voff<false>(lane, wave * 8), vofV = pp_group_voff<true>(lane, wave * 8);
-
-  // Q^T has arrived before the first copy is issued: a wait for it later would also wait for every copy
-  // issued in between (vector-memory operations complete in order)
-#pragma unroll
-  for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[0][ks]));
 
   // one 4-row group: h = 0, 1 (K), 2, 3 (V)
   auto copy_group = [&](const TileSrc &src, int snk, int snv, int h) {
@@ -720,19 +722,25 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     }
   };
 
-  // ---- prologue: tiles kt0 .. kt0+2 start travelling; tile kt0 is waited for ----
+  // ---- prologue: tiles kt0 .. kt0+2 start travelling, then Q^T is fetched.  Vector-memory operations complete
+  // in order, so once Q^T is in its registers (the empty asm makes the compiler wait here, not inside the loop,
+  // where such a wait would drain the copies in flight) the three tiles have landed too. ----
   TilePos pos = tile_pos_init(it.kt0, H.hist_tokens, H.n_sel, H.tpf);
   copy_tile_now(it.kt0, pos, 0, 0);
-  int n_prev = 0, n_last = 0;                                  // copy instructions of the two newest tiles in flight
   if (it.kt0 + 1 < it.kt1) {
     tile_pos_advance(pos, H.n_sel, H.tpf);
-    n_prev = copy_tile_now(it.kt0 + 1, pos, 1, 1);
+    copy_tile_now(it.kt0 + 1, pos, 1, 1);
   }
   if (it.kt0 + 2 < it.kt1) {
     tile_pos_advance(pos, H.n_sel, H.tpf);
-    n_last = copy_tile_now(it.kt0 + 2, pos, 2, 2);
+    copy_tile_now(it.kt0 + 2, pos, 2, 2);
   }
-  wait_copies(n_prev + n_last);
+  bf16x8 qf[1][NKS];
+  attn_load_q<D, 1>(P, it, qf);
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[0][ks]));
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  int n_prev = 0, n_last = 0;                                  // copy instructions of the two newest tiles in flight
   __builtin_amdgcn_s_barrier();
   if (grp == 1) __builtin_amdgcn_s_barrier();                  // group 1 trails by one phase
 
