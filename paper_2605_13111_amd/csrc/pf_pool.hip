@@ -147,10 +147,12 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
   }
 
   // ---- tables: written by the last workgroup of this head to arrive, after every workgroup of the
-  // head has read the old tables (each one read them before it signals its arrival) ----
+  // head has read the old tables.  Each workgroup consumed the old tables (the plan above was computed from
+  // them) before it signals its arrival, and nobody reads the new tables or the payload before the kernel
+  // ends, so the arrival needs no memory fence (a device-scope release here would write back the die's
+  // whole L2 once per workgroup). ----
   __syncthreads();
   if (tid == 0) {
-    __threadfence();
     const int arrived = atomicAdd(&P.sync[h], 1);
     s_last = (arrived == 2 * P.blocks_per_head - 1) ? 1 : 0;
   }
