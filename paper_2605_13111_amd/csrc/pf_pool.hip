@@ -9,10 +9,10 @@
 #include "pf_internal.h"
 
 constexpr int POOL_THREADS = 256;
-constexpr int POOL_UNITS_PER_THREAD = 4;                    // 16-byte units per thread per frame
+constexpr int POOL_UNITS_PER_THREAD = 2;                    // 16-byte units per thread per frame
 constexpr int POOL_CHUNK_UNITS = POOL_THREADS * POOL_UNITS_PER_THREAD;
 constexpr int POOL_MAX_CAND = 2048;                         // resident + new frames of one head
-constexpr int POOL_MOVE_BATCH = 4;                          // frames in flight per thread
+constexpr int POOL_MOVE_BATCH = 8;                          // frames in flight per thread
 
 __global__ void pf_pool_reset_kernel(int32_t *n_frames, int32_t *frame_ids, float *frame_score,
                                      int32_t *T_dev, int32_t *sync, int n_heads, long long total_slots) {
@@ -54,6 +54,7 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
   __shared__ int32_t s_move_src[POOL_MAX_CAND]; // >= 0: resident slot, < 0: -(new index)-1
   __shared__ int32_t s_move_dst[POOL_MAX_CAND];
   __shared__ int32_t s_counts[2];               // kept frames, moves
+  __shared__ int32_t s_wave[POOL_THREADS / 64];
   __shared__ int32_t s_last;
 
   const int h = blockIdx.y;
@@ -99,20 +100,46 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
     s_dest[j] = keep ? 0 : -1;
   }
   __syncthreads();
-  if (tid == 0) {                                             // candidates are few: serial prefix
-    int kept = 0, moves = 0;
-    for (int j = 0; j < n_cand; ++j) {
-      if (s_dest[j] < 0) continue;
-      s_dest[j] = kept;
-      if (j >= n_old || kept != j) {                          // new frame, or a survivor that shifts left
-        s_move_src[moves] = j < n_old ? j : -(j - n_old) - 1;
-        s_move_dst[moves] = kept;
-        ++moves;
+  // destination slots (stable left-pack = exclusive prefix count of the keep flags) and the move list
+  // (new frames, and survivors that shift left), by ballots: 256 candidates per round
+  {
+    const int lane = tid & 63, wave = tid >> 6;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int kept_base = 0, move_base = 0;
+    for (int j0 = 0; j0 < n_cand; j0 += POOL_THREADS) {
+      const int j = j0 + tid;
+      const bool keep = j < n_cand && s_dest[j] >= 0;
+      const unsigned long long km = __builtin_amdgcn_ballot_w64(keep);
+      if (lane == 0) s_wave[wave] = __builtin_popcountll(km);
+      __syncthreads();
+      int dest = kept_base + __builtin_popcountll(km & below), kept_round = 0;
+      for (int w = 0; w < POOL_THREADS / 64; ++w) {
+        if (w < wave) dest += s_wave[w];
+        kept_round += s_wave[w];
       }
-      ++kept;
+      const bool move = keep && (j >= n_old || dest != j);
+      const unsigned long long mm = __builtin_amdgcn_ballot_w64(move);
+      __syncthreads();
+      if (lane == 0) s_wave[wave] = __builtin_popcountll(mm);
+      __syncthreads();
+      int mpos = move_base + __builtin_popcountll(mm & below), moves_round = 0;
+      for (int w = 0; w < POOL_THREADS / 64; ++w) {
+        if (w < wave) mpos += s_wave[w];
+        moves_round += s_wave[w];
+      }
+      if (keep) s_dest[j] = dest;
+      if (move) {
+        s_move_src[mpos] = j < n_old ? j : -(j - n_old) - 1;
+        s_move_dst[mpos] = dest;
+      }
+      kept_base += kept_round;
+      move_base += moves_round;
+      __syncthreads();
     }
-    s_counts[0] = kept;
-    s_counts[1] = moves;
+    if (tid == 0) {
+      s_counts[0] = kept_base;
+      s_counts[1] = move_base;
+    }
   }
   __syncthreads();
   const int n_kept = s_counts[0], n_moves = s_counts[1];
