@@ -576,7 +576,7 @@ template <int B, int E, class F>
 __device__ __forceinline__ void static_for(F &&f) {
   static_for_impl<B>(f, std::make_integer_sequence<int, E - B>());
 }
-constexpr int PP_RING = 7;                                      // fragments requested ahead of their MFMA
+constexpr int PP_RING = 4;                                      // fragments requested ahead of their MFMA
 // LDS reads that fragments i+1 .. last of a matrix phase take (see the kernel: V^T fragments two, K one)
 constexpr int pp_reads_between(int i, int last) {
   int n = 0;
