@@ -32,7 +32,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c3_step", choices=["c2_layer", "c3_step", "c4_skew"])
+    ap.add_argument("--workload", default="c3_step", choices=["c2_layer", "c3_step", "c4_skew", "c5_stream"],
+                    help="c5_stream: streaming rollout, a step = one chunk (4 attention passes over all layers, then "
+                         "append + index build per layer); --steps = chunks from an empty cache (default there: 40)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--cpu-rows", type=int, default=192, help="query rows per head of layer 0 timed on the CPU oracle")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -53,6 +55,8 @@ def main():
     B.lib()                                           # fail loudly if libpf.so is missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.workload == "c5_stream":
+        return stream_bench(args, B, synth, dev)
     w = synth.WORKLOADS[args.workload]
     n_layers = args.layers or w.n_layers
     H, D, tpf = w.n_heads, w.head_dim, w.tokens_per_frame
@@ -212,6 +216,66 @@ def main():
                                             "%.1f s incl. assembling each head's keys)" % (H, len(rows), cpu_flops / 1e9, cpu_s),
                                   "parity_max_abs": float(worst_abs), "parity_rel_l2": float(worst_rel)}
     print(json.dumps(result))
+
+
+def stream_bench(args, B, synth, dev):
+    """Streaming rollout (one-frame chunks): per chunk, 4 denoising passes of 30 attention launches, then the chunk's
+    K/V are appended to every layer's pool and the indices rebuilt.  Everything is enqueued without a host sync."""
+    w = synth.WORKLOADS["c5_stream"]
+    n_layers = args.layers or w.n_layers
+    H, D, tpf = w.n_heads, w.head_dim, w.tokens_per_frame
+    Lq = w.chunk_frames * tpf
+    n_chunks = args.steps if args.steps != 10 else w.history_frames
+    passes = 4
+    layers = []
+    for layer in range(n_layers):
+        pols = synth.policies(w.name, layer=layer)
+        pool = B.Pool(pols, tpf, D, device=dev)
+        index = B.Index(pool, Lq)
+        q = synth.randn_bf16((H, Lq, D), 900000 + layer, device=dev)
+        k_cur = synth.randn_bf16((H, w.chunk_frames, tpf, D), 910000 + layer, device=dev)
+        v_cur = synth.randn_bf16((H, w.chunk_frames, tpf, D), 920000 + layer, device=dev)
+        sc = synth.frame_scores(H, w.chunk_frames, 930000 + layer, device=dev)
+        layers.append((pols, pool, index, q, k_cur, v_cur, sc, torch.empty_like(q)))
+    ws_bytes = max(B.pf_attn_workspace_bytes(L[1], Lq) for L in layers)
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def rollout(chunks):
+        flops = 0.0
+        for (pols, pool, index, *_r) in layers:
+            B.pf_pool_reset(pool)
+            B.pf_build_index(pool, index, Lq)
+        for c in range(chunks):
+            for _ in range(passes):
+                for (pols, pool, index, q, k_cur, v_cur, sc, out) in layers:
+                    B.pf_ragged_attn_fwd(pool, index, q, k_cur.view(H, Lq, D), v_cur.view(H, Lq, D), out, workspace)
+            for (pols, pool, index, q, k_cur, v_cur, sc, out) in layers:
+                flops += passes * sum(4.0 * Lq * (B.pf_selected_count(p, c) * tpf + Lq) * D for p in pols)
+                B.pf_cache_append(pool, k_cur, v_cur, sc)
+                B.pf_build_index(pool, index, Lq)
+        return flops
+
+    rollout(min(args.warmup, n_chunks))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    flops = rollout(n_chunks)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_chunk = wall * 1e3 / n_chunks
+    value = flops / wall / 1e12
+    print(json.dumps({
+        "metric": "ragged-attn effective TFLOP/s (retained keys)", "value": round(value, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": n_chunks, "warmup": min(args.warmup, n_chunks), "ms_per_step": round(ms_per_chunk, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c5_stream: %d layers x %d heads, head_dim %d, %d-token chunks, history 0..%d frames, "
+                               "%d attention passes per chunk" % (n_layers, H, D, Lq, n_chunks - 1, passes),
+                   "step": "one chunk = %d x %d pf_ragged_attn_fwd, then per layer pf_cache_append + pf_build_index; "
+                           "no host sync inside the rollout" % (passes, n_layers),
+                   "effective_tflop_total": round(flops / 1e12, 2), "ms_per_chunk": round(ms_per_chunk, 4)},
+        "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "roofline": {"kernel": "pf_attn_pp_kernel", "bound": "mfma", "achieved": round(value, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(value / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "note": "whole-rollout rate (appends and index builds included in the time)"}}))
 
 
 if __name__ == "__main__":
