@@ -32,9 +32,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c3_step", choices=["c2_layer", "c3_step", "c4_skew", "c5_stream"],
-                    help="c5_stream: streaming rollout, a step = one chunk (4 attention passes over all layers, then "
-                         "append + index build per layer); --steps = chunks from an empty cache (default there: 40)")
+    ap.add_argument("--workload", default="c3_step", choices=["c2_layer", "c3_step", "c4_skew", "c5_stream", "c6_paper"],
+                    help="c5_stream / c6_paper: streaming rollouts, a step = one chunk (4 attention passes over all layers, "
+                         "then append + index build per layer); --steps = chunks from an empty cache (default there: "
+                         "the whole rollout)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--cpu-rows", type=int, default=192, help="query rows per head of layer 0 timed on the CPU oracle")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -55,7 +56,7 @@ def main():
     B.lib()                                           # fail loudly if libpf.so is missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    if args.workload == "c5_stream":
+    if args.workload in ("c5_stream", "c6_paper"):
         return stream_bench(args, B, synth, dev)
     w = synth.WORKLOADS[args.workload]
     n_layers = args.layers or w.n_layers
@@ -219,13 +220,13 @@ def main():
 
 
 def stream_bench(args, B, synth, dev):
-    """Streaming rollout (one-frame chunks): per chunk, 4 denoising passes of 30 attention launches, then the chunk's
+    """Streaming rollout: per chunk, 4 denoising passes of 30 attention launches, then the chunk's
     K/V are appended to every layer's pool and the indices rebuilt.  Everything is enqueued without a host sync."""
-    w = synth.WORKLOADS["c5_stream"]
+    w = synth.WORKLOADS[args.workload]
     n_layers = args.layers or w.n_layers
     H, D, tpf = w.n_heads, w.head_dim, w.tokens_per_frame
     Lq = w.chunk_frames * tpf
-    n_chunks = args.steps if args.steps != 10 else w.history_frames
+    n_chunks = args.steps if args.steps != 10 else w.history_frames // w.chunk_frames
     passes = 4
     layers = []
     for layer in range(n_layers):
@@ -250,7 +251,7 @@ def stream_bench(args, B, synth, dev):
                 for (pols, pool, index, q, k_cur, v_cur, sc, out) in layers:
                     B.pf_ragged_attn_fwd(pool, index, q, k_cur.view(H, Lq, D), v_cur.view(H, Lq, D), out, workspace)
             for (pols, pool, index, q, k_cur, v_cur, sc, out) in layers:
-                flops += passes * sum(4.0 * Lq * (B.pf_selected_count(p, c) * tpf + Lq) * D for p in pols)
+                flops += passes * sum(4.0 * Lq * (B.pf_selected_count(p, c * w.chunk_frames) * tpf + Lq) * D for p in pols)
                 B.pf_cache_append(pool, k_cur, v_cur, sc)
                 B.pf_build_index(pool, index, Lq)
         return flops
@@ -267,8 +268,9 @@ def stream_bench(args, B, synth, dev):
         "metric": "ragged-attn effective TFLOP/s (retained keys)", "value": round(value, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": n_chunks, "warmup": min(args.warmup, n_chunks), "ms_per_step": round(ms_per_chunk, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "c5_stream: %d layers x %d heads, head_dim %d, %d-token chunks, history 0..%d frames, "
-                               "%d attention passes per chunk" % (n_layers, H, D, Lq, n_chunks - 1, passes),
+        "config": {"workload": "%s: %d layers x %d heads, head_dim %d, %d-token chunks, history 0..%d frames, "
+                               "%d attention passes per chunk" % (w.name, n_layers, H, D, Lq, (n_chunks - 1) * w.chunk_frames,
+                                                                  passes),
                    "step": "one chunk = %d x %d pf_ragged_attn_fwd, then per layer pf_cache_append + pf_build_index; "
                            "no host sync inside the rollout" % (passes, n_layers),
                    "effective_tflop_total": round(flops / 1e12, 2), "ms_per_chunk": round(ms_per_chunk, 4)},

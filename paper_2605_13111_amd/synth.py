@@ -28,6 +28,9 @@ WORKLOADS = {
     "c4_skew": Workload("c4_skew", 1, 40, 128, 1560, 3, 60),
     # streaming rollout: 1-frame chunks, 40 chunks, 4 denoising passes per chunk
     "c5_stream": Workload("c5_stream", 30, 12, 128, 1560, 1, 40),
+    # the paper's own policy set (sink 3, recent 4, capacities 4/4/2, strided Anchor, capped Wave) rolled out in
+    # 3-frame chunks to a 240-frame history: mild raggedness, short key lists
+    "c6_paper": Workload("c6_paper", 30, 12, 128, 1560, 3, 240),
 }
 
 
@@ -86,6 +89,8 @@ def policies(workload, layer=0, extra_frames=0):
         return [anchor_all(cap_frames)] * 8 + [veil(1, 3)] * 32
     if w.name in ("c3_step", "c5_stream"):
         return drawn_policies(w.n_heads, 7000 + layer, cap_frames)
+    if w.name == "c6_paper":
+        return paper_default_policies(w.n_heads, 8000 + layer, cap_frames)
     raise KeyError(w.name)
 
 

@@ -172,3 +172,13 @@ def test_c3_layer_sampled_rows():
 def test_c4_skew_sampled_rows():
     """Skewed case: 8 Anchor heads keep all 60 frames, 32 Veil heads keep 4."""
     _full_size("c4_skew", 0, 64, 23, "default")
+
+
+def test_paper_default_policies_at_model_shape(variant):
+    """The paper's own policy set (sink 3, recent 4, capacities 4/4/2: strided Anchor, capped Wave with its sliding
+    retention window, Veil) after 14 three-frame chunks (42 history frames) at model shape: pool, index and
+    cu_seqlens bit-exact, attention on sampled rows."""
+    pols = synth.paper_default_policies(12, 8003, 48)
+    rows = G.sample_rows(4680, 48, 31, extra=(1559, 1560, 3119, 3120))
+    a, r = G.run_case(pols, 1560, 128, [3] * 14, 4680, seed=31, rows=rows, check_every_append=False, label="paper-default")
+    print("paper-default policies: max-abs %.2e rel %.2e" % (a, r))
