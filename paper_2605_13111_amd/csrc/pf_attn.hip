@@ -712,14 +712,15 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   // "at most n vector-memory operations outstanding", n = the copy instructions of the two newest tiles
   // (0, 4 or 16 each)
   auto wait_copies = [&](int n) {
-    switch (n) {
-      case 4: __builtin_amdgcn_s_waitcnt(0x0F70 | 4); break;
-      case 8: __builtin_amdgcn_s_waitcnt(0x0F70 | 8); break;
-      case 16: __builtin_amdgcn_s_waitcnt(0x0F70 | (16 & 15) | ((16 >> 4) << 14)); break;
-      case 20: __builtin_amdgcn_s_waitcnt(0x0F70 | (20 & 15) | ((20 >> 4) << 14)); break;
-      case 32: __builtin_amdgcn_s_waitcnt(0x0F70 | (32 & 15) | ((32 >> 4) << 14)); break;
-      default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+    if (n == 8) {                                               // two contiguous tiles in flight: the common case
+      __builtin_amdgcn_s_waitcnt(0x0F70 | 8);
+      return;
     }
+    if (n == 4) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);
+    else if (n == 16) __builtin_amdgcn_s_waitcnt(0x0F70 | (16 & 15) | ((16 >> 4) << 14));
+    else if (n == 20) __builtin_amdgcn_s_waitcnt(0x0F70 | (20 & 15) | ((20 >> 4) << 14));
+    else if (n == 32) __builtin_amdgcn_s_waitcnt(0x0F70 | (32 & 15) | ((32 >> 4) << 14));
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
   };
 
   // ---- prologue: tiles kt0 .. kt0+2 start travelling, then Q^T is fetched.  Vector-memory operations complete
