@@ -10,8 +10,10 @@ frame index ``t``).  Every head has the parameters
     mode    Anchor only: 0 ALL, 1 STRIDED, 2 TOPK
     sink    S  shared sink frames               (Sec. 4.2, last paragraph)
     recent  R  force-preserved recent frames    (Sec. 4.2, last paragraph)
-    cap     Cap, 0 = unlimited                  (Eq. 4, Eq. 5)
-    period  P, Wave only                        (Eq. 5, Observation 2)
+    cap     Cap, 0 = unlimited                  (Eq. 4, Eq. 5); Veil: number of merged
+                                                frames, 0 = no cache merging
+    period  P, Wave                             (Eq. 5, Observation 2); Veil: size m of
+                                                the local window that is merged (Sec. 4.2)
 
 The head-type policy acts on the *intermediate* history between the sink and
 the recent window (Sec. 4.2, last paragraph), written ``middle`` below.
@@ -22,6 +24,7 @@ against the paper by eye.
 
 ANCHOR, WAVE, VEIL = 0, 1, 2
 MODE_ALL, MODE_STRIDED, MODE_TOPK = 0, 1, 2
+MERGED = 1 << 30        # flag of a merged-frame entry: MERGED | id of the window's first frame
 
 
 def sink_frames(T, S):
@@ -82,10 +85,39 @@ def wave_periodic(T, middle, period, cap):
     return set(picks)
 
 
+def veil_windows(T, S, R, cap, m):
+    """Cache merging of Veil heads (Sec. 4.2): the local windows of m frames that are each compressed into one
+    merged frame.  Window j (j = 0 nearest) covers the m frames right before the previous window, starting from
+    the forced recent frames: ids T-R-(j+1)m .. T-R-jm-1; a window exists only if it lies entirely in the
+    intermediate history.  Returns the first frame ids of the existing windows, ascending."""
+    starts = []
+    for j in range(cap):
+        w0 = T - R - (j + 1) * m
+        if m >= 1 and w0 >= S:
+            starts.append(w0)
+    return sorted(starts)
+
+
+def merged_rows(m, tokens_per_frame):
+    """Composition of a merged frame (Sec. 4.2, K_merged = Concat_i K[t-m+i, C_i]): list of (i, token) pairs, one
+    per row, where frame i of the window contributes its i-th 1/m subset C_i = {token : token mod m == i}."""
+    rows = []
+    for i in range(m):
+        for tok in range(tokens_per_frame):
+            if tok % m == i:
+                rows.append((i, tok))
+    return rows
+
+
 def selected_frames(pol, T, score_of=None):
-    """Ascending list of the frame ids head ``pol`` attends to when the chunk
-    starting at id T is generated: sink + recent + type policy on the middle."""
+    """List of the frames head ``pol`` attends to when the chunk starting at id T is generated, in the order of
+    its key sequence: sink + type policy on the middle + recent, ascending ids.  A Veil head with cache merging
+    has entries MERGED | w0 (one per merged window, ascending) between its sink and its recent frames."""
     middle = middle_frames(T, pol.sink, pol.recent)
+    if pol.type == VEIL and pol.cap > 0:
+        sink = sorted(sink_frames(T, pol.sink))
+        recent = sorted(recent_frames(T, pol.recent) - set(sink))
+        return sink + [MERGED | w0 for w0 in veil_windows(T, pol.sink, pol.recent, pol.cap, pol.period)] + recent
     if pol.type == ANCHOR:
         if pol.mode == MODE_ALL:
             typed = set(middle)
@@ -117,7 +149,8 @@ def retained_frames(pol, T_new, candidates, score_of=None):
       Wave, Cap = 0         every frame;
       Wave, Cap > 0         sink + recent + every id >= T_new - (floor(R/P)+Cap)*P,
                             the oldest id a later chunk can still pick;
-      Veil                  sink + recent.
+      Veil                  sink + recent; with cache merging also the Cap*m frames before the recent
+                            ones (the sources of this and every later step's merged windows).
     """
     cand = sorted(candidates)
     keep = sink_frames(T_new, pol.sink) | recent_frames(T_new, pol.recent)
@@ -133,7 +166,8 @@ def retained_frames(pol, T_new, candidates, score_of=None):
             oldest = T_new - (pol.recent // pol.period + pol.cap) * pol.period
             keep |= {f for f in cand if f >= oldest}
     elif pol.type == VEIL:
-        pass
+        if pol.cap > 0:
+            keep |= {f for f in cand if f >= T_new - pol.recent - pol.cap * pol.period}
     else:
         raise ValueError("bad head policy")
     return [f for f in cand if f in keep]

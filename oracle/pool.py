@@ -43,11 +43,42 @@ class PoolOracle:
             score_of = {f[0]: f[1] for f in cand}
             keep = set(P.retained_frames(pol, T_new, [f[0] for f in cand], score_of))
             kept = [f for f in cand if f[0] in keep]
-            if len(kept) > pol.slots:
-                raise CapacityError("head %d needs %d slots, has %d" % (h, len(kept), pol.slots))
+            if len(kept) > pol.slots - self.merged_slots(pol):
+                raise CapacityError("head %d needs %d slots, has %d" % (h, len(kept), pol.slots - self.merged_slots(pol)))
             staged.append(kept)
         self.frames = staged                            # nothing changes if any head overflowed
         self.T = T_new
+
+    # ----------------------------------------------------------- cache merging
+    @staticmethod
+    def merged_slots(pol):
+        """Slots at the end of a head's region reserved for merged frames (Veil heads with cache merging)."""
+        return pol.cap if (pol.type == P.VEIL and pol.cap > 0) else 0
+
+    def merged_frame(self, h, w0):
+        """K, V (uint16 [tpf, D]) of the merged frame of the window starting at frame w0 (Sec. 4.2): row r is token
+        ``tok`` of frame w0+i for the r-th (i, tok) pair of ``policy.merged_rows``."""
+        pol = self.policies[h]
+        by_id = {f[0]: f for f in self.frames[h]}
+        K = np.zeros((self.tpf, self.D), np.uint16)
+        V = np.zeros((self.tpf, self.D), np.uint16)
+        for r, (i, tok) in enumerate(P.merged_rows(pol.period, self.tpf)):
+            K[r] = by_id[w0 + i][2][tok]
+            V[r] = by_id[w0 + i][3][tok]
+        return K, V
+
+    def merged_windows(self, h):
+        """[(local slot, w0)] of the merged frames head h holds at the current history length: window j
+        (0 = nearest) sits in the head's slot ``slots - 1 - j``."""
+        pol = self.policies[h]
+        if not self.merged_slots(pol):
+            return []
+        out = []
+        for j in range(pol.cap):
+            w0 = self.T - pol.recent - (j + 1) * pol.period
+            if w0 >= pol.sink:
+                out.append((pol.slots - 1 - j, w0))
+        return out
 
     # ------------------------------------------------------------------ layout
     def slot_base(self):
@@ -67,14 +98,19 @@ class PoolOracle:
             for j, f in enumerate(fr):
                 frame_ids[base[h] + j] = f[0]
                 frame_score[base[h] + j] = f[1]
+            for slot, w0 in self.merged_windows(h):
+                frame_ids[base[h] + slot] = P.MERGED | w0
         return n_frames, frame_ids, frame_score
 
     def resident_kv(self):
-        """Yield (global_slot, K, V) for every resident frame."""
+        """Yield (global_slot, K, V) for every resident frame, merged frames included."""
         base = self.slot_base()
         for h, fr in enumerate(self.frames):
             for j, f in enumerate(fr):
                 yield base[h] + j, f[2], f[3]
+            for slot, w0 in self.merged_windows(h):
+                K, V = self.merged_frame(h, w0)
+                yield base[h] + slot, K, V
 
     # ------------------------------------------------------------------- index
     def build_index(self, max_sel):
@@ -88,6 +124,7 @@ class PoolOracle:
         for h, pol in enumerate(self.policies):
             score_of = {f[0]: f[1] for f in self.frames[h]}
             where = {f[0]: j for j, f in enumerate(self.frames[h])}
+            where.update({P.MERGED | w0: slot for slot, w0 in self.merged_windows(h)})
             sel = P.selected_frames(pol, self.T, score_of)
             assert len(sel) <= max_sel
             sel_count[h] = len(sel)
@@ -100,8 +137,14 @@ class PoolOracle:
     def head_kv(self, h, frame_ids):
         """Concatenated K, V (uint16 [len*tpf, D]) of the given frames of head h."""
         by_id = {f[0]: f for f in self.frames[h]}
-        ks = [by_id[f][2] for f in frame_ids]
-        vs = [by_id[f][3] for f in frame_ids]
+        ks, vs = [], []
+        for f in frame_ids:
+            if f & P.MERGED:
+                K, V = self.merged_frame(h, f & ~P.MERGED)
+            else:
+                K, V = by_id[f][2], by_id[f][3]
+            ks.append(K)
+            vs.append(V)
         if not ks:
             z = np.zeros((0, self.D), np.uint16)
             return z, z

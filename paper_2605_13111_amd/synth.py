@@ -60,6 +60,14 @@ def veil(sink, recent, slots=None):
     return HeadPolicy(VEIL, 0, sink, recent, 0, 1, slots if slots is not None else sink + recent)
 
 
+def veil_merged(sink, recent, n_merged, window, slots=None):
+    """Veil head with cache merging (Sec. 4.2): ``n_merged`` merged frames, each compressing a local window of
+    ``window`` frames.  Pool region: sink + recent + the window sources + the frames of one append, plus one slot
+    per merged frame at the end of the region."""
+    need = sink + recent + n_merged * window + 3 + n_merged
+    return HeadPolicy(VEIL, 0, sink, recent, n_merged, window, slots if slots is not None else need)
+
+
 def drawn_policies(n_heads, seed, max_frames, topk_cap=18, veil_recent=3):
     """Head types drawn 40/30/30 (Anchor/Wave/Veil) from the seed; Anchor = TOPK with ``topk_cap``,
     Wave period uniform in {2,3,4} and uncapped, Veil = 1 sink + ``veil_recent`` adjacent frames."""

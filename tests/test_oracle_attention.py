@@ -165,3 +165,39 @@ def test_float32_evaluation_agrees():
 def test_widen_bf16_is_exact():
     x = synth.randn_bf16((1000,), 3)
     assert np.array_equal(A.widen_bf16(synth.bits(x)), x.float().numpy())
+
+
+@pytest.mark.parametrize("m,tpf", [(2, 6), (3, 7)])
+def test_veil_cache_merging_equals_a_token_level_mask(m, tpf):
+    """A merged frame is a concatenation of token subsets of raw frames, and softmax attention does not depend on
+    the order of its keys: attending to [sink | merged windows | recent | chunk] must equal dense attention over
+    EVERY raw token with the mask 'token tok of frame w0+i is visible iff tok mod m == i' written down here."""
+    H, D, T, Lq = 2, 64, 17, 5
+    S, R, cap = 2, 3, 2
+    pols = [synth.veil_merged(S, R, cap, m), synth.veil_merged(1, 0, 1, m)]
+    k_hist = synth.randn_bf16((H, T, tpf, D), 71)
+    v_hist = synth.randn_bf16((H, T, tpf, D), 72)
+    q = synth.randn_bf16((H, Lq, D), 73)
+    k_cur = synth.randn_bf16((H, Lq, D), 74)
+    v_cur = synth.randn_bf16((H, Lq, D), 75)
+    pool = PoolOracle(pols, tpf, D)
+    for t in range(T):
+        pool.append(synth.bits(k_hist[:, t:t + 1]), synth.bits(v_hist[:, t:t + 1]))
+    out = _oracle_out(pool, pols, q, k_cur, v_cur)
+    k_all = torch.cat([k_hist.reshape(H, T * tpf, D), k_cur], 1).double().numpy()
+    v_all = torch.cat([v_hist.reshape(H, T * tpf, D), v_cur], 1).double().numpy()
+    mask = np.zeros((H, T * tpf + Lq), bool)
+    mask[:, T * tpf:] = True
+    for h, (s_, r_, c_) in enumerate([(S, R, cap), (1, 0, 1)]):
+        for f in list(range(s_)) + list(range(T - r_, T)):
+            mask[h, f * tpf:(f + 1) * tpf] = True
+        for j in range(c_):
+            w0 = T - r_ - (j + 1) * m
+            assert w0 >= s_
+            for i in range(m):
+                for tok in range(tpf):
+                    if tok % m == i:
+                        mask[h, (w0 + i) * tpf + tok] = True
+    want, _ = dense_masked_attention(q.double().numpy(), k_all, v_all, mask, 1.0 / math.sqrt(D))
+    assert [int(x.sum()) for x in mask] == [(S + R + cap) * tpf + Lq, (1 + 1) * tpf + Lq]
+    assert np.abs(out - want).max() < 1e-6

@@ -144,3 +144,35 @@ def test_cu_seqlens_is_an_exclusive_prefix_sum():
     cu = P.cu_seqlens(counts, 1560)
     assert cu[0] == 0 and cu[-1] == 1560 * sum(counts)
     assert all(cu[i + 1] - cu[i] == counts[i] * 1560 for i in range(40))
+
+
+# ---------------------------------------------------------------- Veil cache merging (Sec. 4.2)
+def test_veil_merging_windows_and_key_sequence():
+    """Paper defaults for Veil heads: sink 3, forced recent 4, 2 merged frames, window 2.  At T = 20 the recent
+    frames are 16..19, so the windows are [14,16) and [12,14); each is ONE entry of the key sequence."""
+    pol = synth.veil_merged(3, 4, 2, 2)
+    M = P.MERGED
+    assert P.selected_frames(pol, 20) == [0, 1, 2, M | 12, M | 14, 16, 17, 18, 19]
+    # a window exists only if it lies entirely between the sink and the recent frames
+    assert P.selected_frames(pol, 9) == [0, 1, 2, M | 3, 5, 6, 7, 8]            # [3,5) fits, [1,3) does not
+    assert P.selected_frames(pol, 8) == [0, 1, 2, 4, 5, 6, 7]                   # [2,4) overlaps the sink
+    assert P.selected_frames(pol, 5) == [0, 1, 2, 3, 4]                         # sink and recent overlap
+    assert P.selected_frames(pol, 0) == []
+    # without forced recent frames the window is the m frames before the current one: merged(t-m : t)
+    assert P.selected_frames(synth.veil_merged(1, 0, 1, 3), 10) == [0, M | 7]
+    # retention: sink, recent, and the Cap*m frames the windows of this and any later step are made of
+    assert P.retained_frames(pol, 20, range(20)) == [0, 1, 2] + list(range(12, 20))
+    # cap = 0 is the plain Veil policy
+    assert P.selected_frames(synth.veil(3, 4), 20) == [0, 1, 2, 16, 17, 18, 19]
+
+
+def test_merged_frame_composition():
+    """Frame i of the window contributes the tokens congruent to i modulo m, in order; the pieces are
+    concatenated in window order and add up to exactly one frame of tokens, also when m does not divide it."""
+    assert P.merged_rows(2, 6) == [(0, 0), (0, 2), (0, 4), (1, 1), (1, 3), (1, 5)]
+    assert P.merged_rows(3, 7) == [(0, 0), (0, 3), (0, 6), (1, 1), (1, 4), (2, 2), (2, 5)]
+    for m in (1, 2, 3, 4, 5):
+        for tpf in (1, 7, 16, 1560):
+            rows = P.merged_rows(m, tpf)
+            assert len(rows) == tpf and sorted(t for _, t in rows) == list(range(tpf))   # every token position once
+            assert all(t % m == i for i, t in rows)

@@ -18,6 +18,36 @@ def _frames(H, n, tpf, D, first_id):
     return k, v
 
 
+def test_veil_merging_pool_layout_and_streaming():
+    """Merged frames sit in the last slots of the head's region (window j, 0 = nearest, in slot slots-1-j), are
+    rebuilt from the raw frames at every history length, and the raw frames a later window needs stay resident."""
+    tpf, D = 6, 8
+    pol = synth.veil_merged(2, 3, 2, 2)
+    pool = PoolOracle([pol], tpf, D)
+    k, v = _frames(1, 30, tpf, D, 0)
+    for t in range(30):
+        pool.append(k[:, t:t + 1], v[:, t:t + 1])
+        T = t + 1
+        n, ids, _ = pool.tables()
+        raw = [f for f in range(T) if f < 2 or f >= T - 3 - 4]
+        assert list(ids[:n[0]]) == raw and n[0] <= pol.slots - 2
+        for j in range(2):
+            w0 = T - 3 - (j + 1) * 2
+            slot = pol.slots - 1 - j
+            if w0 >= 2:
+                assert ids[slot] == (P.MERGED | w0)
+                K, V = pool.merged_frame(0, w0)
+                assert np.array_equal(K[0], k[0, w0, 0]) and np.array_equal(K[tpf // 2], k[0, w0 + 1, 1])
+                assert np.array_equal(V[tpf - 1], v[0, w0 + 1, tpf - 1])
+            else:
+                assert ids[slot] == -1
+    # streaming == batch: one append of everything gives the same state
+    batch = PoolOracle([synth.veil_merged(2, 3, 2, 2, slots=40)], tpf, D)
+    batch.append(k, v)
+    assert [f[0] for f in batch.frames[0]] == [f[0] for f in pool.frames[0]]
+    assert batch.merged_windows(0)[0][1] == pool.merged_windows(0)[0][1]
+
+
 def _mixed_policies(max_frames):
     return [synth.anchor_all(max_frames), synth.anchor_topk(5, 5), synth.anchor_topk(4, 9, sink=2, recent=3),
             synth.wave(3, max_frames), synth.wave(2, 16, cap=3, sink=1, recent=2), synth.veil(1, 3),
