@@ -62,17 +62,29 @@ extern "C" {
  *                   (ties: smaller id first);
  *   Wave            T - i*period, i = 1,2,... (Eq. 5 / Observation 2), the cap
  *                   nearest ones if cap > 0;
- *   Veil            none.
- * cap = 0 means unlimited.  `slots` is the capacity, in frames, of this head's
- * region of the pool.
+ *   Veil            none if cap = 0.  With cap > 0, cache merging (Sec. 4.2): cap merged
+ *                   frames, each compressing a local window of `period` = m frames.
+ *                   Window j (0 = nearest) covers ids T-R-(j+1)m .. T-R-jm-1 and exists
+ *                   if it lies entirely in the intermediate range; its merged frame is
+ *                   the concatenation over i = 0..m-1 of the tokens of frame w0+i whose
+ *                   index is congruent to i modulo m (tokens_per_frame tokens in all).
+ *                   In the head's key sequence the merged frames stand between the sink
+ *                   and the recent frames, oldest window first; sel_frames holds
+ *                   PF_MERGED_FRAME | w0 for them (w0 = first frame of the window).
+ *                   The pool keeps them in the LAST cap slots of the head's region
+ *                   (window j in slot slots-1-j), rebuilt by every pf_cache_append; raw
+ *                   frames may use slots - cap slots.
+ * cap = 0 means unlimited (Anchor, Wave).  `slots` is the capacity, in frames, of this
+ * head's region of the pool.
  */
+#define PF_MERGED_FRAME (1 << 30)
 typedef struct pf_head_policy {
   int32_t type;      /* PF_ANCHOR | PF_WAVE | PF_VEIL */
   int32_t mode;      /* PF_MODE_*, Anchor only (0 otherwise) */
   int32_t sink;      /* S >= 0 */
   int32_t recent;    /* R >= 0 */
   int32_t cap;       /* Cap >= 0, 0 = unlimited */
-  int32_t period;    /* P >= 1, Wave only (ignored otherwise) */
+  int32_t period;    /* Wave: P >= 1; Veil with cap > 0: window size m >= 1; ignored otherwise */
   int32_t slots;     /* >= 1 */
   int32_t reserved;  /* must be 0 */
 } pf_head_policy;

@@ -14,6 +14,7 @@ static bool policy_ok(const pf_head_policy &p) {
   if (p.type == PF_ANCHOR && (p.mode < PF_MODE_ALL || p.mode > PF_MODE_TOPK)) return false;
   if (p.sink < 0 || p.recent < 0 || p.cap < 0 || p.slots < 1) return false;
   if (p.type == PF_WAVE && p.period < 1) return false;
+  if (p.type == PF_VEIL && p.cap > 0 && (p.cap > 64 || p.period < 1 || p.period > 64 || p.slots <= p.cap)) return false;
   return true;
 }
 

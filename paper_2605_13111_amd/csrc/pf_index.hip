@@ -87,6 +87,9 @@ __global__ __launch_bounds__(INDEX_THREADS) void pf_build_index_kernel(IndexPara
     const int mid_lo = pol.sink, mid_hi = P.T - pol.recent;
     const bool need_rank = pol.type == PF_ANCHOR && pol.mode == PF_MODE_TOPK && pol.cap > 0 &&
                            pf_middle_count(P.T, pol.sink, pol.recent) > pol.cap;
+    // Veil heads with cache merging: their merged frames (kept in the last slots of the region) stand between
+    // the sink and the recent frames in the key sequence, oldest window first
+    const int n_win = pf_veil_windows(pol, P.T);
     int n = 0;
     for (int j0 = 0; j0 < n_res; j0 += 64) {
       const int j = j0 + lane;
@@ -107,13 +110,21 @@ __global__ __launch_bounds__(INDEX_THREADS) void pf_build_index_kernel(IndexPara
         sel = frame_selected(pol, P.T, f, rank);
       }
       const unsigned long long mask = __builtin_amdgcn_ballot_w64(sel);
-      const int pos = n + __builtin_popcountll(mask & ((1ull << lane) - 1ull));
+      const int pos = n + __builtin_popcountll(mask & ((1ull << lane) - 1ull)) + (f >= pol.sink ? n_win : 0);
       if (sel && pos < P.max_sel) {
         P.sel_frames[(size_t)h * P.max_sel + pos] = f;
         P.sel_slots[(size_t)h * P.max_sel + pos] = base + j;
       }
       n += __builtin_popcountll(mask);
     }
+    if (lane < n_win) {                                           // window j = lane, 0 = nearest
+      const int pos = pf_min(pol.sink, P.T) + (n_win - 1 - lane);
+      if (pos < P.max_sel) {
+        P.sel_frames[(size_t)h * P.max_sel + pos] = PF_MERGED_FRAME | (P.T - pol.recent - (lane + 1) * pol.period);
+        P.sel_slots[(size_t)h * P.max_sel + pos] = base + pol.slots - 1 - lane;
+      }
+    }
+    n += n_win;
     if (lane == 0) {
       P.sel_count[h] = n;
       s_selcount[h] = n;

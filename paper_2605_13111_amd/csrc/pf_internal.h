@@ -39,6 +39,15 @@ PF_HD int pf_wave_middle_picks(int T, int S, int R, int P) {
   return pf_max(0, i_last - i_first + 1);
 }
 
+// Veil cache merging (Sec. 4.2): slots at the end of the head's region that hold merged frames, and the number
+// of merged windows (m = period frames each, stacked before the recent frames) that fit into the intermediate
+// range at history length T.
+PF_HD int pf_veil_merged_slots(const pf_head_policy &p) { return (p.type == PF_VEIL && p.cap > 0) ? p.cap : 0; }
+PF_HD int pf_veil_windows(const pf_head_policy &p, int T) {
+  if (p.type != PF_VEIL || p.cap <= 0) return 0;
+  return pf_min(p.cap, pf_middle_count(T, p.sink, p.recent) / p.period);
+}
+
 // Frames head `p` attends to when the history has T frames.
 PF_HD int pf_sel_count_impl(const pf_head_policy &p, int T) {
   const int mid = pf_middle_count(T, p.sink, p.recent);
@@ -49,6 +58,8 @@ PF_HD int pf_sel_count_impl(const pf_head_policy &p, int T) {
   } else if (p.type == PF_WAVE) {
     typed = pf_wave_middle_picks(T, p.sink, p.recent, p.period);
     if (p.cap > 0) typed = pf_min(typed, p.cap);
+  } else {
+    typed = pf_veil_windows(p, T);                 // one merged frame per window
   }
   return shared + typed;
 }
@@ -73,6 +84,8 @@ PF_HD int pf_ret_count_impl(const pf_head_policy &p, int T) {
       kept = pf_max(0, (T - p.recent) - lo);
       kept = pf_min(kept, mid);
     }
+  } else if (p.cap > 0) {
+    kept = pf_min(mid, p.cap * p.period);          // the sources of this and every later step's windows
   }
   return shared + kept;
 }

@@ -44,7 +44,8 @@ struct PoolAppendParams {
 __device__ __forceinline__ bool middle_kept(const pf_head_policy &p, int T, int f, int rank) {
   if (p.type == PF_ANCHOR) return (p.mode == PF_MODE_TOPK && p.cap > 0) ? rank < p.cap : true;
   if (p.type == PF_WAVE) return p.cap <= 0 ? true : f >= pf_wave_oldest(p, T);
-  return false;   // Veil: sink + recent only
+  // Veil: sink + recent only; with cache merging also the frames the merged windows are (and will be) made of
+  return p.cap > 0 && f >= T - p.recent - p.cap * p.period;
 }
 
 __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppendParams P) {
@@ -204,6 +205,56 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Veil cache merging (Sec. 4.2): after an append, rebuild the merged frames of every Veil head that
+// has them.  Window j (0 = nearest) of head h covers frames w0 .. w0+m-1 with w0 = T-R-(j+1)m and goes to the
+// head's slot slots-1-j; row r of the merged frame is token `tok` of frame w0+i, where (i, tok) runs over
+// i = 0..m-1 and, inside i, over the tokens congruent to i modulo m.  The sources are found in closed form:
+// a head's resident raw frames are its sink frames followed by the ids lo .. T-1, lo = max(S, T-R-cap*m).
+// grid: (16-byte units of a frame / 256, heads * max_cap, K|V).
+// ---------------------------------------------------------------------------------------------------
+struct PoolMergeParams {
+  uint4 *k_pool, *v_pool;
+  const pf_head_policy *policy;
+  const int32_t *slot_base;
+  int32_t *frame_ids;
+  float *frame_score;
+  int T, tpf, row_units, frame_units, max_cap;
+};
+
+__global__ __launch_bounds__(POOL_THREADS) void pf_pool_merge_kernel(PoolMergeParams P) {
+  const int h = blockIdx.y / P.max_cap, j = blockIdx.y % P.max_cap;
+  const pf_head_policy pol = P.policy[h];
+  if (pol.type != PF_VEIL || j >= pol.cap) return;
+  const int m = pol.period;
+  const int w0 = P.T - pol.recent - (j + 1) * m;
+  const bool exists = w0 >= pol.sink;
+  const int base = P.slot_base[h];
+  const int dst_slot = base + pol.slots - 1 - j;
+  if (blockIdx.x == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
+    P.frame_ids[dst_slot] = exists ? (PF_MERGED_FRAME | w0) : -1;
+    P.frame_score[dst_slot] = 0.0f;
+  }
+  if (!exists) return;
+  const int u = blockIdx.x * POOL_THREADS + threadIdx.x;
+  if (u >= P.frame_units) return;
+  const int r = u / P.row_units, c = u - r * P.row_units;
+  // row r -> (i, tok): subset i holds the tokens i, i+m, i+2m, ... below tpf
+  int i = 0, first = 0;
+  for (; i < m; ++i) {
+    const int n_i = (P.tpf - i + m - 1) / m;
+    if (r < first + n_i) break;
+    first += n_i;
+  }
+  const int tok = (r - first) * m + i;
+  const int f = w0 + i;
+  const int n_sink = pf_min(pol.sink, P.T);
+  const int lo = pf_max(pol.sink, P.T - pol.recent - pol.cap * m);
+  const int src_slot = base + (f < pol.sink ? f : n_sink + (f - lo));
+  uint4 *pool = blockIdx.z ? P.v_pool : P.k_pool;
+  pool[(size_t)dst_slot * P.frame_units + u] = pool[(size_t)src_slot * P.frame_units + (size_t)tok * P.row_units + c];
+}
+
 extern "C" int pf_pool_reset(pf_pool *pool, void *stream) {
   const int rc = pf_validate_pool(pool);
   if (rc != PF_OK) return rc;
@@ -227,7 +278,7 @@ extern "C" int pf_cache_append(pf_pool *pool, const void *k_new, const void *v_n
   const int T_new = pool->T_host + n_new;
   for (int h = 0; h < pool->n_heads; ++h) {
     const pf_head_policy &p = pool->policy_host[h];
-    if (pf_ret_count_impl(p, T_new) > p.slots) return PF_ERR_CAPACITY;
+    if (pf_ret_count_impl(p, T_new) > p.slots - pf_veil_merged_slots(p)) return PF_ERR_CAPACITY;
     if (pf_ret_count_impl(p, pool->T_host) + n_new > POOL_MAX_CAND) return PF_ERR_CAPACITY;
   }
   PoolAppendParams P;
@@ -250,6 +301,26 @@ extern "C" int pf_cache_append(pf_pool *pool, const void *k_new, const void *v_n
   hipLaunchKernelGGL(pf_pool_append_kernel, dim3(P.blocks_per_head, pool->n_heads, 2), dim3(POOL_THREADS), 0,
                      (hipStream_t)stream, P);
   PF_HIP_CHECK(hipGetLastError());
+  // heads with cache merging: a second launch rebuilds their merged frames from the frames just packed
+  int max_cap = 0;
+  for (int h = 0; h < pool->n_heads; ++h) max_cap = pf_max(max_cap, pf_veil_merged_slots(pool->policy_host[h]));
+  if (max_cap > 0) {
+    PoolMergeParams M;
+    M.k_pool = (uint4 *)pool->k_pool;
+    M.v_pool = (uint4 *)pool->v_pool;
+    M.policy = pool->policy_dev;
+    M.slot_base = pool->slot_base;
+    M.frame_ids = pool->frame_ids;
+    M.frame_score = pool->frame_score;
+    M.T = T_new;
+    M.tpf = pool->tokens_per_frame;
+    M.row_units = pool->head_dim / 8;
+    M.frame_units = P.frame_units;
+    M.max_cap = max_cap;
+    hipLaunchKernelGGL(pf_pool_merge_kernel, dim3(pf_ceil_div(P.frame_units, POOL_THREADS), pool->n_heads * max_cap, 2),
+                       dim3(POOL_THREADS), 0, (hipStream_t)stream, M);
+    PF_HIP_CHECK(hipGetLastError());
+  }
   pool->T_host = T_new;
   return PF_OK;
 }

@@ -103,8 +103,8 @@ def policies(workload, layer=0, extra_frames=0):
 
 
 def paper_default_policies(n_heads, seed, max_frames, wave_period=6):
-    """The paper's own hyper-parameters (experimental setup): sink 3, forced recent 4,
-    capacities Anchor/Wave/Veil 4/4/2 (Veil without merging keeps sink + recent only)."""
+    """The paper's own hyper-parameters (experimental setup): sink 3, forced recent 4, capacities
+    Anchor/Wave/Veil 4/4/2, Veil merge window 2."""
     g = _cpu_gen(seed)
     u = torch.rand(n_heads, generator=g)
     pols = []
@@ -114,7 +114,7 @@ def paper_default_policies(n_heads, seed, max_frames, wave_period=6):
         elif u[h] < 0.7:
             pols.append(wave(wave_period, min(max_frames, 3 + 4 + 5 * wave_period), cap=4, sink=3, recent=4))
         else:
-            pols.append(veil(3, 4))
+            pols.append(veil_merged(3, 4, 2, 2))
     return pols
 
 

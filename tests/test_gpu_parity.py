@@ -182,3 +182,17 @@ def test_paper_default_policies_at_model_shape(variant):
     rows = G.sample_rows(4680, 48, 31, extra=(1559, 1560, 3119, 3120))
     a, r = G.run_case(pols, 1560, 128, [3] * 14, 4680, seed=31, rows=rows, check_every_append=False, label="paper-default")
     print("paper-default policies: max-abs %.2e rel %.2e" % (a, r))
+
+
+def test_veil_cache_merging(variant):
+    """Veil heads with cache merging (Sec. 4.2) next to the other head types: merged frames bit-exact in the pool
+    after every append (windows of 2 and of 3 frames, token counts that 3 does and does not divide), merged
+    entries in the index, attention over [sink | merged | recent | chunk]."""
+    pols = [synth.veil_merged(3, 4, 2, 2), synth.veil_merged(1, 2, 1, 3), synth.veil_merged(1, 0, 3, 2), synth.veil(1, 3),
+            synth.anchor_all(24), synth.wave(3, 24)]
+    a, r = G.run_case(pols, 200, 128, [3] * 7, 600, seed=41, label="veil-merging")
+    a, r = G.run_case(pols[:4], 17, 64, [1] * 15, 40, seed=42, label="veil-merging-small")
+    # the paper's defaults for Veil heads at model shape, sampled rows
+    pols = [synth.veil_merged(3, 4, 2, 2)] * 2 + synth.paper_default_policies(4, 8005, 40)
+    rows = G.sample_rows(4680, 32, 43, extra=(1559, 1560))
+    G.run_case(pols, 1560, 128, [3] * 9, 4680, seed=43, rows=rows, check_every_append=False, label="veil-merging-model")

@@ -35,6 +35,9 @@ def _policies():
                 out.append(synth.HeadPolicy(synth.ANCHOR, synth.MODE_TOPK, S, R, cap, 1, 100))
                 for period in (1, 2, 3, 6):
                     out.append(synth.HeadPolicy(synth.WAVE, 0, S, R, cap, period, 100))
+            for cap in (1, 2, 3):                      # Veil with cache merging: cap merged frames, window m
+                for m in (1, 2, 3, 5):
+                    out.append(synth.HeadPolicy(synth.VEIL, 0, S, R, cap, m, 100))
     return out
 
 
@@ -54,6 +57,9 @@ def test_count_helpers_reject_bad_policies():
     assert B.pf_selected_count(bad, 3) == B.PF_ERR_INVALID_ARG
     assert B.pf_retained_count(synth.HeadPolicy(synth.WAVE, 0, 0, 0, 0, 0, 4), 3) == B.PF_ERR_INVALID_ARG
     assert B.pf_selected_count(synth.anchor_all(4), -1) == B.PF_ERR_INVALID_ARG
+    # cache merging needs a window size and room for the merged frames next to the raw ones
+    assert B.pf_selected_count(synth.HeadPolicy(synth.VEIL, 0, 1, 2, 2, 0, 16), 9) == B.PF_ERR_INVALID_ARG
+    assert B.pf_selected_count(synth.HeadPolicy(synth.VEIL, 0, 1, 2, 2, 2, 2), 9) == B.PF_ERR_INVALID_ARG
 
 
 def _fake_pool(policies, tpf=16, D=64):
