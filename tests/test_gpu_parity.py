@@ -196,3 +196,54 @@ def test_veil_cache_merging(variant):
     pols = [synth.veil_merged(3, 4, 2, 2)] * 2 + synth.paper_default_policies(4, 8005, 40)
     rows = G.sample_rows(4680, 32, 43, extra=(1559, 1560))
     G.run_case(pols, 1560, 128, [3] * 9, 4680, seed=43, rows=rows, check_every_append=False, label="veil-merging-model")
+
+
+def test_index_and_attention_replay_from_a_hip_graph():
+    """The library enqueues kernels only (no allocation, no synchronisation, no memset): one layer's index build +
+    attention captured into a HIP graph replays bit-identically to the eager launches, also with other work and
+    synchronisations between the replays and after the inputs have changed."""
+    dev = "cuda:0"
+    pols = _mixed(12)
+    tpf, D, Lq, H = 48, 128, 200, len(pols)
+    pool = B.Pool(pols, tpf, D, device=dev)
+    B.pf_pool_reset(pool)
+    for ci in range(4):
+        B.pf_cache_append(pool, synth.randn_bf16((H, 3, tpf, D), 50 + ci).to(dev), synth.randn_bf16((H, 3, tpf, D), 60 + ci).to(dev),
+                          synth.frame_scores(H, 3, 70 + ci).to(dev))
+    index = B.Index(pool, Lq, seg_tiles=16)                       # short segments: split heads, partials, merges
+    q = synth.randn_bf16((H, Lq, D), 80).to(dev)
+    k_cur = synth.randn_bf16((H, Lq, D), 81).to(dev)
+    v_cur = synth.randn_bf16((H, Lq, D), 82).to(dev)
+    out = torch.zeros_like(q)
+    ws = torch.empty(1 << 26, dtype=torch.uint8, device=dev)
+
+    def run():
+        B.pf_build_index(pool, index, Lq)
+        B.pf_ragged_attn_fwd(pool, index, q, k_cur, v_cur, out, ws)
+
+    run()
+    torch.cuda.synchronize()
+    eager = out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        run()                                                     # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        out.fill_(float("nan"))
+        (q * 2).sum().item()                                      # unrelated eager work + a synchronisation
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), "replay %d differs" % rep
+    q.copy_(synth.randn_bf16((H, Lq, D), 83).to(dev))             # new inputs, same buffers
+    run()
+    torch.cuda.synchronize()
+    eager2 = out.clone()
+    out.fill_(float("nan"))
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), eager2.view(torch.int16)) and not torch.equal(eager, eager2)
