@@ -545,11 +545,13 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void pf_attn_kernel(AttnParams P) {
 // wave of a SIMD issues the 32 MFMAs of a tile (O^T += V^T P^T of the previous tile, then S^T = K Q^T of
 // the current one) the other computes its softmax on the vector ALU.  A workgroup barrier ends every phase
 // and keeps the groups in step.
-//   phase M(u)   reads K of tile u and V of tile u-1, issues the copies of tile u+2 into the stage tile u-2
-//                lived in (its last readers, both groups' M(u-1), are two barriers back), and ends with the
-//                wait for this wave's copies of tile u+1
-//   phase V(u)   scores of tile u -> weights (masking of the ragged tail, lazy rescaling as in the
-//                rescaling loop); requests the first V^T fragments of tile u for the next matrix phase
+//   phase M(u)   reads K of tile u and V of tile u-1 and ends with the wait for this wave's copies of tile u+1
+//   phase V(u)   requests the first V^T fragments of tile u for the next matrix phase, sends the copies of
+//                tile u+3 into the stages tiles u-1 (K) and u-2 (V) lived in (their last readers, both groups'
+//                M(u-1), are two barriers back), plans the copy after that, then scores of tile u -> weights
+//                (masking of the ragged tail, lazy rescaling as in the rescaling loop)
+// A wave is limited by its own instruction stream (about one instruction per 5 cycles, an MFMA ~16), and the
+// matrix phase is the longer one, so the copies and their address arithmetic sit in the vector phase.
 // K/V tiles travel global -> LDS three tiles ahead (K ring of 4 stages, V ring of 5: V of a tile is read one
 // phase after its K) with 16-byte copies: one instruction
 // moves four 256-byte rows (lane i -> bytes 16*i of the 1 KB destination), a quarter of the instructions the
@@ -666,7 +668,6 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   attn_zero<D, 1>(o, m_run, l_run);
   const float c = P.scale_log2;
   const float thr = ATT_LAZY_LOG2 / c;
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
   // LDS byte addresses of this lane's fragments inside stage 0 (other stages: + stage * PP_TILE_BYTES).  The
   // arrays are 1 KB aligned, so the chunk permutation and the k-step / channel-block index act on address
@@ -682,19 +683,28 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     const int c0 = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
     av = ldsV + rowv * 256 + ((c0 ^ pp_swz(true, rowv)) << 4) + 8 * (lane & 1);
   }
-  // per-lane source offsets of this wave's first 4-row copy group; the second group's (rows + 4) differ in
-  // one bit for K and not at all for V
-  const unsigned vofK = pp_group_voff<false>(lane, wave * 8), vofV = pp_group_voff<true>(lane, wave * 8);
+  // per-lane source offsets inside a 4-row copy group; the wave's second group (rows + 4) differs in one bit
+  // for K and not at all for V
+  const unsigned vofK0 = pp_group_voff<false>(lane, wave * 8), vofK1 = vofK0 ^ 64u, vofV = pp_group_voff<true>(lane, wave * 8);
+  const int wrow_bytes = wave * 8 * 256;                       // this wave's first row inside a tile
 
-  // one 4-row group: h = 0, 1 (K), 2, 3 (V)
+  // One 4-row group: h = 0, 1 (K), 2, 3 (V).  The copies are buffer loads: the tile's first row is the base of a
+  // 16 KB buffer descriptor (scalar registers), the wave's rows are a scalar offset, the lane's chunk a 32-bit
+  // vector offset that never changes, and the second group is the instruction's immediate offset (it moves the
+  // LDS destination along with the source).  Next to MFMAs this form costs almost nothing, whereas a global
+  // load with a 64-bit address per lane held up the SIMD for ~65 cycles per instruction (measured).
   auto copy_group = [&](const TileSrc &src, int snk, int snv, int h) {
-    const int r0 = wave * 8 + 4 * (h & 1);
+    constexpr unsigned RSRC_FLAGS = 0x00020000u;               // raw buffer, 32-bit data format
     if (h < 2) {
-      const char *b = (const char *)src.kb + r0 * 256;
-      __builtin_amdgcn_global_load_lds((gptr_t)(b + (vofK ^ ((h & 1) << 6))), (lptr_t)(&sK[snk][r0 * 256]), 16, 0, 0);
+      const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)src.kb, 0, PP_TILE_BYTES, RSRC_FLAGS);
+      lptr_t dst = (lptr_t)(&sK[snk][wrow_bytes]);
+      if (h == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofK0, wrow_bytes, 0, 0);
+      else __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofK1, wrow_bytes, 1024, 0);
     } else {
-      const char *b = (const char *)src.vb + r0 * 256;
-      __builtin_amdgcn_global_load_lds((gptr_t)(b + vofV), (lptr_t)(&sV[snv][r0 * 256]), 16, 0, 0);
+      const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)src.vb, 0, PP_TILE_BYTES, RSRC_FLAGS);
+      lptr_t dst = (lptr_t)(&sV[snv][wrow_bytes]);
+      if (h == 2) __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofV, wrow_bytes, 0, 0);
+      else __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofV, wrow_bytes, 1024, 0);
     }
   };
   // whole tile at once (prologue, and tiles that cross a frame border or hold the ragged end)
@@ -709,17 +719,10 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     pp_copy_rows_slow<true>(kt, H, sV[snv], wave, lane);
     return 16;
   };
-  // "at most n vector-memory operations outstanding", n = the copy instructions of the two newest tiles
-  // (0, 4 or 16 each)
+  // "at most n vector-memory operations outstanding", n = the copy instructions of the newest tile (0, 4 or 16)
   auto wait_copies = [&](int n) {
-    if (n == 8) {                                               // two contiguous tiles in flight: the common case
-      __builtin_amdgcn_s_waitcnt(0x0F70 | 8);
-      return;
-    }
-    if (n == 4) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);
+    if (n == 4) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);        // a contiguous tile in flight: the common case
     else if (n == 16) __builtin_amdgcn_s_waitcnt(0x0F70 | (16 & 15) | ((16 >> 4) << 14));
-    else if (n == 20) __builtin_amdgcn_s_waitcnt(0x0F70 | (20 & 15) | ((20 >> 4) << 14));
-    else if (n == 32) __builtin_amdgcn_s_waitcnt(0x0F70 | (32 & 15) | ((32 >> 4) << 14));
     else __builtin_amdgcn_s_waitcnt(0x0F70);
   };
 
@@ -741,7 +744,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[0][ks]));
   __builtin_amdgcn_s_waitcnt(0x0F70);
-  int n_prev = 0, n_last = 0;                                  // copy instructions of the two newest tiles in flight
+  int n_last = 0;                                              // copy instructions sent in the last vector phase
   __builtin_amdgcn_s_barrier();
   if (grp == 1) __builtin_amdgcn_s_barrier();                  // group 1 trails by one phase
 
@@ -774,27 +777,33 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     }
   };
 
-  // ---- plan of the next copy (made in the vector phase, where the scalar load of the frame's slot is off
-  // the matrix path; carried out in the following matrix phase, when the target stages are free) ----
+  // ---- plan of the next copy (made in one vector phase and carried out at the start of the next, so the
+  // scalar load of a frame's slot has a whole tile time to arrive) ----
   TileSrc nsrc;
   nsrc.kb = nsrc.vb = nullptr;
   nsrc.simple = false;
-  int ncopy_kt = -1;                                           // tile to copy in the next matrix phase, -1: none
+  int ncopy_kt = -1;                                           // tile planned for the next copy, -1: none
+  int run_left = 0;                                            // tiles after the planned one that continue its source run
   auto plan_copy = [&](int kt_target) {
+    if (__builtin_expect(run_left > 0, 1)) {
+      // common case: the tile follows a contiguous tile of the same frame (or of the chunk), is itself whole and
+      // inside it, and belongs to this work item: both sources move on by one tile, no slot lookup
+      --run_left;
+      pos.r += PF_BK;
+      nsrc.kb += PF_BK * D;
+      nsrc.vb += PF_BK * D;
+      ncopy_kt = kt_target;
+      return;
+    }
     ncopy_kt = -1;
     if (kt_target < it.kt1) {
-      const int j_prev = pos.j;
       tile_pos_advance(pos, H.n_sel, H.tpf);
-      // common case: the tile follows a contiguous tile of the same frame (or of the chunk) and is itself whole
-      // and inside it: both sources move on by one tile, no slot lookup
-      const bool whole = H.lkv - kt_target * PF_BK >= PF_BK && (pos.j >= H.n_sel || pos.r + PF_BK <= H.tpf);
-      if (nsrc.simple && pos.j == j_prev && whole) {
-        nsrc.kb += PF_BK * D;
-        nsrc.vb += PF_BK * D;
-      } else {
-        nsrc = tile_src(kt_target, pos, H, D);
-      }
+      nsrc = tile_src(kt_target, pos, H, D);
       ncopy_kt = kt_target;
+      if (nsrc.simple) {
+        const int room = pos.j < H.n_sel ? H.tpf - pos.r : H.lkv - kt_target * PF_BK;   // keys from the tile's first row to the run's end
+        run_left = pf_min(room / PF_BK - 1, it.kt1 - 1 - kt_target);
+      }
     }
   };
 
@@ -804,22 +813,6 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     constexpr bool HAS_PV = decltype(has_pv)::value, HAS_QK = decltype(has_qk)::value;
     constexpr int FIRST = HAS_PV ? 0 : 16, LAST = HAS_QK ? 31 : 15;
     const unsigned offK = st_qk * PP_TILE_BYTES, offV = st_pv * PP_TILE_BYTES;
-    // copies of the planned tile (three ahead of the QK tile): K into the stage after next of the K ring (tile
-    // kt-1's), V into the stage before st_pv (tile kt-2's); the four 4-row groups go out between the MFMAs
-    const int snk = (st_qk + 3) & (PP_KSTAGES - 1);
-    const int snv = st_pv >= 1 ? st_pv - 1 : PP_VSTAGES - 1;
-    bool inl = false;
-    int n_sent = 0;
-    if (HAS_QK && ncopy_kt >= 0) {
-      if (nsrc.simple) {
-        inl = true;
-        n_sent = 4;
-      } else {
-        pp_copy_rows_slow<false>(ncopy_kt, H, sK[snk], wave, lane);
-        pp_copy_rows_slow<true>(ncopy_kt, H, sV[snv], wave, lane);
-        n_sent = 16;
-      }
-    }
     __builtin_amdgcn_s_setprio(3);                              // the matrix phase goes first on its SIMD
     if constexpr (!HAS_PV) static_for<16, 16 + PP_RING>([&](auto f) { issue_frag(f, offK, offV); });
     static_for<FIRST, LAST + 1>([&](auto f) {
@@ -828,26 +821,35 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
       wait_frag(f, IntC<NEWEST>());
       mfma_frag(f);
       if constexpr (I + PP_RING <= LAST) issue_frag(IntC<I + PP_RING>(), offK, offV);
-      if constexpr (HAS_QK && (I - FIRST) % 4 == 3 && (I - FIRST) / 4 < 4) {
-        if (inl) copy_group(nsrc, snk, snv, (I - FIRST) / 4);
-      }
       __builtin_amdgcn_sched_barrier(0);                        // keep the hand-made order: wait, MFMA, next request
     });
     __builtin_amdgcn_s_setprio(0);
-    if (HAS_QK) {
-      // this wave's rows of the tile after the QK tile have landed once only the copies of the two tiles
-      // behind it are outstanding
-      n_prev = n_last;
-      n_last = n_sent;
-      wait_copies(n_prev + n_last);
-    }
+    // this wave's rows of the tile after the QK tile (sent two vector phases ago) have landed once only the
+    // copies of its last vector phase are outstanding
+    if (HAS_QK) wait_copies(n_last);
     __builtin_amdgcn_s_barrier();
   };
 
   // ---- vector phase: scores of tile kt -> weights; requests the first V^T fragments of tile kt (V stage
   // sv) for the next matrix phase and plans that phase's copy ----
-  auto v_phase = [&](int kt, int sv_) {
+  auto v_phase = [&](int kt, int sk_, int sv_) {
     static_for<0, PP_RING>([&](auto f) { issue_frag(f, 0u, (unsigned)(sv_ * PP_TILE_BYTES)); });
+    // the copy planned one vector phase ago: tile kt+3, K into the stage tile kt-1 lived in, V into tile kt-2's
+    // (their last readers, both groups' M(kt-1), are two barriers back)
+    n_last = 0;
+    if (ncopy_kt >= 0) {
+      const int snk = (sk_ + 3) & (PP_KSTAGES - 1);
+      const int snv = sv_ >= 2 ? sv_ - 2 : sv_ + PP_VSTAGES - 2;
+      if (nsrc.simple) {
+#pragma unroll
+        for (int h = 0; h < 4; ++h) copy_group(nsrc, snk, snv, h);
+        n_last = 4;
+      } else {
+        pp_copy_rows_slow<false>(ncopy_kt, H, sK[snk], wave, lane);
+        pp_copy_rows_slow<true>(ncopy_kt, H, sV[snv], wave, lane);
+        n_last = 16;
+      }
+    }
     plan_copy(kt + 4);
     const int valid = H.lkv - kt * BK;                          // ragged tail: only the head's last tile
     if (valid < BK) {
@@ -874,30 +876,34 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
         for (int i = 0; i < 16; ++i) o[0][db][i] *= alpha;
     }
     const float mc = m_run[0] * c;
+    // row sum with plain fp32 adds: a dot-product instruction goes through the matrix pipe and queues there
+    // behind the other group's MFMAs (measured: ~54 cycles each next to a saturated MFMA stream, against 4 alone)
+    float ls0 = 0.f, ls1 = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
-        bf16x2 pk;
-        pk[0] = (__bf16)fast_exp2(fmaf(s[kb][i], c, -mc));
-        pk[1] = (__bf16)fast_exp2(fmaf(s[kb][i + 1], c, -mc));
-        l_run[0] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run[0], false);
-        pf[kb * 2 + (i >> 3)][i & 7] = pk[0];
-        pf[kb * 2 + (i >> 3)][(i & 7) + 1] = pk[1];
+        const float e0 = fast_exp2(fmaf(s[kb][i], c, -mc));
+        const float e1 = fast_exp2(fmaf(s[kb][i + 1], c, -mc));
+        ls0 += e0;
+        ls1 += e1;
+        pf[kb * 2 + (i >> 3)][i & 7] = (__bf16)e0;
+        pf[kb * 2 + (i >> 3)][(i & 7) + 1] = (__bf16)e1;
       }
+    l_run[0] += ls0 + ls1;
     __builtin_amdgcn_s_barrier();
   };
 
   int sk = 0, sv = 0;                                          // K and V stage of the tile whose scores are computed
   plan_copy(it.kt0 + 3);
   m_phase(TagF(), TagT(), 0, PP_VSTAGES - 1);                  // "the V stage before tile kt0's"
-  v_phase(it.kt0, 0);
+  v_phase(it.kt0, 0, 0);
   for (int kt = it.kt0 + 1; kt < it.kt1; ++kt) {
     const int sp = sv;
     sk = (sk + 1) & (PP_KSTAGES - 1);
     sv = sv + 1 == PP_VSTAGES ? 0 : sv + 1;
     m_phase(TagT(), TagT(), sk, sp);
-    v_phase(kt, sv);
+    v_phase(kt, sk, sv);
   }
   m_phase(TagT(), TagF(), 0, sv);
   if (grp == 0) __builtin_amdgcn_s_barrier();                  // group 0 waits for group 1's last phase
