@@ -721,7 +721,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   };
   // "at most n vector-memory operations outstanding", n = the copy instructions of the newest tile (0, 4 or 16)
   auto wait_copies = [&](int n) {
-    if (n == 4) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);        // a contiguous tile in flight: the common case
+    if (__builtin_expect(n == 4, 1)) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);   // a contiguous tile in flight: the common case
     else if (n == 16) __builtin_amdgcn_s_waitcnt(0x0F70 | (16 & 15) | ((16 >> 4) << 14));
     else __builtin_amdgcn_s_waitcnt(0x0F70);
   };
@@ -837,10 +837,10 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     // the copy planned one vector phase ago: tile kt+3, K into the stage tile kt-1 lived in, V into tile kt-2's
     // (their last readers, both groups' M(kt-1), are two barriers back)
     n_last = 0;
-    if (ncopy_kt >= 0) {
+    if (__builtin_expect(ncopy_kt >= 0, 1)) {
       const int snk = (sk_ + 3) & (PP_KSTAGES - 1);
       const int snv = sv_ >= 2 ? sv_ - 2 : sv_ + PP_VSTAGES - 2;
-      if (nsrc.simple) {
+      if (__builtin_expect(nsrc.simple, 1)) {
 #pragma unroll
         for (int h = 0; h < 4; ++h) copy_group(nsrc, snk, snv, h);
         n_last = 4;
@@ -852,7 +852,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     }
     plan_copy(kt + 4);
     const int valid = H.lkv - kt * BK;                          // ragged tail: only the head's last tile
-    if (valid < BK) {
+    if (__builtin_expect(valid < BK, 0)) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -865,7 +865,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
     mx = partner_max(mx);
-    if (__builtin_amdgcn_ballot_w64(mx > m_run[0] + thr) != 0) {
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx > m_run[0] + thr) != 0, 0)) {
       const float m_new = fmaxf(m_run[0], mx);
       const float alpha = fast_exp2((m_run[0] - m_new) * c);
       m_run[0] = m_new;
