@@ -37,6 +37,9 @@ def parse():
                          "then append + index build per layer); --steps = chunks from an empty cache (default there: "
                          "the whole rollout)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
+    ap.add_argument("--layout", default="packed", choices=["packed", "model"],
+                    help="chunk tensors per head [heads][tokens][D] (default) or as the model holds them, "
+                         "[tokens][heads][D], through the strided entry point")
     ap.add_argument("--cpu-rows", type=int, default=192, help="query rows per head of layer 0 timed on the CPU oracle")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
@@ -104,7 +107,9 @@ def main():
         q = synth.randn_bf16((H, Lq, D), 900000 + layer, device=dev)
         k_cur = synth.randn_bf16((H, Lq, D), 910000 + layer, device=dev)
         v_cur = synth.randn_bf16((H, Lq, D), 920000 + layer, device=dev)
-        out = torch.empty_like(q)
+        if args.layout == "model":                 # same values, held as [tokens][heads][D]; the views are heads-first
+            q, k_cur, v_cur = [t.permute(1, 0, 2).contiguous().permute(1, 0, 2) for t in (q, k_cur, v_cur)]
+        out = torch.empty_like(q)                  # preserves the strides
         layers.append((pool, index, q, k_cur, v_cur, out))
     ws_bytes = max(B.pf_attn_workspace_bytes(L[0], Lq) for L in layers)
     workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)     # layers run one after another: shared
@@ -117,6 +122,8 @@ def main():
     side = torch.cuda.Stream()
     built = [torch.cuda.Event() for _ in layers]
 
+    attn_fwd = B.pf_ragged_attn_fwd_strided if args.layout == "model" else B.pf_ragged_attn_fwd
+
     def step(events=None):
         side.wait_stream(main)                     # the previous step's launches have read their plans
         with torch.cuda.stream(side):
@@ -128,7 +135,7 @@ def main():
             if events is not None:
                 e0, e1 = ev(), ev()
                 e0.record()
-            B.pf_ragged_attn_fwd(pool, index, q, k_cur, v_cur, out, workspace)
+            attn_fwd(pool, index, q, k_cur, v_cur, out, workspace)
             if events is not None:
                 e1.record()
                 events.append((e0, e1))
@@ -175,7 +182,7 @@ def main():
                                "%d history frames" % (w.name, n_layers, H, D, tpf, Lq, T),
                    "step": "per layer pf_build_index (side stream) + pf_ragged_attn_fwd, %d layers back to back" % n_layers,
                    "effective_tflop_per_step": round(flops / 1e12, 3),
-                   "attn_variant": int(layers[0][1].c.variant),
+                   "attn_variant": int(layers[0][1].c.variant), "chunk_layout": args.layout,
                    "seg_tiles": int(os.environ.get("PF_SEG_TILES", "0")) or "default"},
         "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "roofline": {"kernel": "pf_attn_pp_kernel" if int(layers[0][1].c.variant) == 1 else "pf_attn_kernel", "bound": "mfma", "achieved": round(achieved, 2),

@@ -145,6 +145,22 @@ typedef struct pf_index {
   int32_t reserved;               /* segment length the library chose (0 when the caller fixed it); start at 0 */
 } pf_index;
 
+/*
+ * Layout of the chunk tensors when they are not packed per head.  The model keeps
+ * its activations as [tokens][heads][head_dim] (the attention of Eq. 1 is applied
+ * to projections of that shape), so the strided entry points read q / k_cur / v_cur
+ * / k_new / v_new and write out in place, without a permute pass before or after
+ * (the per-call packing the fused kernel of Sec. 4.3 removes).
+ * Strides are in ELEMENTS: element (head h, token t, channel d) sits at
+ * base + h*head_stride + t*token_stride + d.  Both must be multiples of 8
+ * (16-byte rows), >= head_dim, and rows must not overlap: either
+ * head_stride >= tokens*token_stride or token_stride >= n_heads*head_stride.
+ */
+typedef struct pf_chunk_layout {
+  int64_t token_stride;
+  int64_t head_stride;
+} pf_chunk_layout;
+
 /* ---- sizes (host only, no device access) -------------------------------- */
 
 /* Bytes of pf_index.work needed for a pool with these policies, for any T the
@@ -183,6 +199,13 @@ int pf_pool_reset(pf_pool *pool, void *stream);
 int pf_cache_append(pf_pool *pool, const void *k_new, const void *v_new,
                     int n_new, const float *scores, void *stream);
 
+/* The same with k_new / v_new laid out by `layout` (token index = frame*tokens_per_frame
+ * + token inside the frame, n_new*tokens_per_frame tokens): the write-back reads the
+ * chunk's keys and values where the attention pass left them.  layout must not be NULL. */
+int pf_cache_append_strided(pf_pool *pool, const void *k_new, const void *v_new,
+                            int n_new, const float *scores,
+                            const pf_chunk_layout *layout, void *stream);
+
 /*
  * Select every head's frames for the chunk that starts at frame id T
  * (Sec. 4.2 policies), map them to pool slots, write cu_seqlens (Sec. 4.3) and
@@ -207,6 +230,15 @@ int pf_ragged_attn_fwd(const pf_pool *pool, const pf_index *index,
                        const void *q, const void *k_cur, const void *v_cur, void *out,
                        int q_tokens, float softmax_scale,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* The same with q, k_cur, v_cur and out laid out by `layout` (one layout for all
+ * four; q_tokens tokens).  layout must not be NULL.  Chunk key tiles are then
+ * fetched row by row; history tiles are unaffected. */
+int pf_ragged_attn_fwd_strided(const pf_pool *pool, const pf_index *index,
+                               const void *q, const void *k_cur, const void *v_cur, void *out,
+                               int q_tokens, float softmax_scale,
+                               void *workspace, size_t workspace_bytes,
+                               const pf_chunk_layout *layout, void *stream);
 
 /* Human-readable text for a status code (static storage). */
 const char *pf_status_string(int status);

@@ -15,11 +15,16 @@ LIB_PATH = os.path.join(HERE, "libpf.so")
 PF_OK, PF_ERR_INVALID_ARG, PF_ERR_CAPACITY, PF_ERR_UNSUPPORTED, PF_ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["pf_index_work_bytes", "pf_attn_workspace_bytes", "pf_selected_count", "pf_retained_count",
-           "pf_pool_reset", "pf_cache_append", "pf_build_index", "pf_ragged_attn_fwd", "pf_status_string"]
+           "pf_pool_reset", "pf_cache_append", "pf_cache_append_strided", "pf_build_index", "pf_ragged_attn_fwd",
+           "pf_ragged_attn_fwd_strided", "pf_status_string"]
 
 
 class pf_head_policy(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("type", "mode", "sink", "recent", "cap", "period", "slots", "reserved")]
+
+
+class pf_chunk_layout(ctypes.Structure):
+    _fields_ = [("token_stride", ctypes.c_int64), ("head_stride", ctypes.c_int64)]
 
 
 class pf_pool(ctypes.Structure):
@@ -64,10 +69,15 @@ def lib():
         L.pf_pool_reset.argtypes = [P(pf_pool), V]
         L.pf_cache_append.restype = I
         L.pf_cache_append.argtypes = [P(pf_pool), V, V, I, V, V]
+        L.pf_cache_append_strided.restype = I
+        L.pf_cache_append_strided.argtypes = [P(pf_pool), V, V, I, V, P(pf_chunk_layout), V]
         L.pf_build_index.restype = I
         L.pf_build_index.argtypes = [P(pf_pool), P(pf_index), I, V]
         L.pf_ragged_attn_fwd.restype = I
         L.pf_ragged_attn_fwd.argtypes = [P(pf_pool), P(pf_index), V, V, V, V, I, ctypes.c_float, V, ctypes.c_size_t, V]
+        L.pf_ragged_attn_fwd_strided.restype = I
+        L.pf_ragged_attn_fwd_strided.argtypes = [P(pf_pool), P(pf_index), V, V, V, V, I, ctypes.c_float, V, ctypes.c_size_t,
+                                                 P(pf_chunk_layout), V]
         L.pf_status_string.restype = ctypes.c_char_p
         L.pf_status_string.argtypes = [I]
         _lib = L
@@ -192,6 +202,20 @@ def pf_cache_append(pool, k_new, v_new, scores=None, stream=None):
                                  _stream(stream)), "pf_cache_append")
 
 
+def pf_cache_append_strided(pool, k_new, v_new, scores=None, stream=None):
+    """k_new, v_new: bf16 views of logical shape [n_heads, n_new, tokens_per_frame, head_dim] whose tokens are
+    equally spaced (e.g. a [tokens, heads, head_dim] tensor seen as heads x frames x tokens); no copy is made."""
+    assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16
+    assert tuple(k_new.shape) == (pool.n_heads, k_new.shape[1], pool.tpf, pool.D) and v_new.shape == k_new.shape
+    assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1 and k_new.stride(1) == pool.tpf * k_new.stride(2)
+    if scores is not None:
+        assert scores.is_contiguous() and scores.dtype == torch.float32
+        assert tuple(scores.shape) == (pool.n_heads, k_new.shape[1])
+    lay = pf_chunk_layout(k_new.stride(2), k_new.stride(0))
+    _check(lib().pf_cache_append_strided(ctypes.byref(pool.c), _ptr(k_new), _ptr(v_new), int(k_new.shape[1]),
+                                         _ptr(scores), ctypes.byref(lay), _stream(stream)), "pf_cache_append_strided")
+
+
 def pf_build_index(pool, index, q_tokens, stream=None):
     _check(lib().pf_build_index(ctypes.byref(pool.c), ctypes.byref(index.c), int(q_tokens), _stream(stream)),
            "pf_build_index")
@@ -206,3 +230,17 @@ def pf_ragged_attn_fwd(pool, index, q, k_cur, v_cur, out, workspace, softmax_sca
     _check(lib().pf_ragged_attn_fwd(ctypes.byref(pool.c), ctypes.byref(index.c), _ptr(q), _ptr(k_cur), _ptr(v_cur),
                                     _ptr(out), int(q.shape[1]), float(softmax_scale), _ptr(workspace), ws_bytes,
                                     _stream(stream)), "pf_ragged_attn_fwd")
+
+
+def pf_ragged_attn_fwd_strided(pool, index, q, k_cur, v_cur, out, workspace, softmax_scale=0.0, stream=None):
+    """q, k_cur, v_cur, out: bf16 views of logical shape [n_heads, q_tokens, head_dim] with one common stride
+    pattern (e.g. [tokens, heads, head_dim] tensors permuted to heads first); no copy is made."""
+    for t in (q, k_cur, v_cur, out):
+        assert t.dtype == torch.bfloat16 and tuple(t.shape) == tuple(q.shape) and t.stride() == q.stride()
+    assert q.shape[0] == pool.n_heads and q.shape[2] == pool.D and q.stride(2) == 1
+    lay = pf_chunk_layout(q.stride(1), q.stride(0))
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().pf_ragged_attn_fwd_strided(ctypes.byref(pool.c), ctypes.byref(index.c), _ptr(q), _ptr(k_cur),
+                                            _ptr(v_cur), _ptr(out), int(q.shape[1]), float(softmax_scale),
+                                            _ptr(workspace), ws_bytes, ctypes.byref(lay), _stream(stream)),
+           "pf_ragged_attn_fwd_strided")

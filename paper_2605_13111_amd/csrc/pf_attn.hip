@@ -44,6 +44,9 @@ struct AttnParams {
   float *workspace;
   int max_sel, tpf, q_tokens, n_qt;
   float scale_log2;     // softmax scale * log2(e)
+  // chunk tensors (q, k_cur, v_cur, out): element strides between tokens of a head and between heads
+  // (packed [heads][tokens][D]: D and q_tokens*D; the model's [tokens][heads][D]: heads*D and D)
+  long long tok_stride, head_stride;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -111,6 +114,7 @@ struct HeadKV {     // everything a loader thread needs to find keys of one head
   int n_sel, tpf, hist_tokens, lkv;
   int lrow, lchunk;
   unsigned thread_off;
+  long long cur_stride;   // elements between consecutive chunk tokens in k_cur / v_cur
 };
 
 // Global -> register load of one 64-key tile of one tensor.  Common case (tile inside one frame, no ragged
@@ -123,11 +127,15 @@ __device__ __forceinline__ void attn_load_rows(u32x4 (&reg)[NP], int kt, TilePos
   const int last = H.lkv - 1 - kt * PF_BK;
   const bool in_hist = pos.j < H.n_sel;
   const bool simple = last >= PF_BK - 1 && (!in_hist || pos.r + PF_BK <= H.tpf);
-  if (simple) {
+  if (simple && (in_hist || H.cur_stride == D)) {
     const char *b = in_hist ? (const char *)(pool + ((size_t)H.slots[pos.j] * H.tpf + pos.r) * D)
                             : (const char *)(cur + (size_t)pos.r * D);
 #pragma unroll
     for (int p = 0; p < NP; ++p) reg[p] = *(const u32x4 *)(b + (H.thread_off + p * PASS_BYTES));
+  } else if (simple) {                              // whole chunk tile, token rows apart by the caller's stride
+    const __bf16 *b = cur + (size_t)pos.r * H.cur_stride + H.lchunk * 8;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) reg[p] = *(const u32x4 *)(b + (size_t)(H.lrow + p * RPP) * H.cur_stride);
   } else {
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
@@ -136,7 +144,7 @@ __device__ __forceinline__ void attn_load_rows(u32x4 (&reg)[NP], int kt, TilePos
       const int th = in_chunk ? 0 : t;
       const int j = th / H.tpf;
       const size_t e_hist = ((size_t)pf_max(H.slots[j], 0) * H.tpf + (th - j * H.tpf)) * D;
-      const size_t e = in_chunk ? (size_t)(t - H.hist_tokens) * D : e_hist;
+      const size_t e = in_chunk ? (size_t)(t - H.hist_tokens) * H.cur_stride : e_hist;
       const __bf16 *b = in_chunk ? cur : pool;
       reg[p] = *(const u32x4 *)(b + e + H.lchunk * 8);
     }
@@ -151,7 +159,8 @@ __device__ __forceinline__ void attn_store_rows(const u32x4 (&reg)[NP], __bf16 *
 
 // Where a tile's rows come from, for the direct global -> LDS copies of the two-group kernel.
 struct TileSrc {
-  bool simple;            // tile inside one frame (or the chunk) and not ragged: base + row * D
+  bool simple;            // tile inside one frame (or the chunk) and not ragged: base + row * stride
+  bool strided;           // simple chunk tile whose rows are cur_stride elements apart instead of D
   const __bf16 *kb, *vb;  // first row of the tile (simple case)
   int kt;
 };
@@ -160,9 +169,10 @@ __device__ __forceinline__ TileSrc tile_src(int kt, TilePos pos, const HeadKV &H
   const int last = H.lkv - 1 - kt * PF_BK;
   const bool in_hist = pos.j < H.n_sel;
   t.simple = last >= PF_BK - 1 && (!in_hist || pos.r + PF_BK <= H.tpf);
+  t.strided = !in_hist && H.cur_stride != D;
   t.kt = kt;
   size_t e = 0;
-  if (t.simple) e = in_hist ? ((size_t)H.slots[pos.j] * H.tpf + pos.r) * D : (size_t)pos.r * D;
+  if (t.simple) e = in_hist ? ((size_t)H.slots[pos.j] * H.tpf + pos.r) * D : (size_t)pos.r * H.cur_stride;
   t.kb = (in_hist ? H.k_pool : H.k_cur) + e;
   t.vb = (in_hist ? H.v_pool : H.v_cur) + e;
   return t;
@@ -355,7 +365,7 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
   }
   __syncthreads();
 
-  __bf16 *oh = P.out + (size_t)h * P.q_tokens * D;
+  __bf16 *oh = P.out + (size_t)h * P.head_stride;
   if (it.nseg == 1) {
     for (int e = tid; e < BQ * (D / 8); e += NT) {
       const int r = e / (D / 8), d0 = (e % (D / 8)) * 8;
@@ -366,7 +376,7 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
       bf16x8 w;
       w[0] = (__bf16)(a.x * inv); w[1] = (__bf16)(a.y * inv); w[2] = (__bf16)(a.z * inv); w[3] = (__bf16)(a.w * inv);
       w[4] = (__bf16)(b.x * inv); w[5] = (__bf16)(b.y * inv); w[6] = (__bf16)(b.z * inv); w[7] = (__bf16)(b.w * inv);
-      *(bf16x8 *)(oh + (size_t)row * D + d0) = w;
+      *(bf16x8 *)(oh + (size_t)row * P.tok_stride + d0) = w;
     }
     return;
   }
@@ -451,7 +461,7 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
       w[2] = (__bf16)(acc[k][0].z * inv); w[3] = (__bf16)(acc[k][0].w * inv);
       w[4] = (__bf16)(acc[k][1].x * inv); w[5] = (__bf16)(acc[k][1].y * inv);
       w[6] = (__bf16)(acc[k][1].z * inv); w[7] = (__bf16)(acc[k][1].w * inv);
-      *(bf16x8 *)(oh + (size_t)row * D + d0[k]) = w;
+      *(bf16x8 *)(oh + (size_t)row * P.tok_stride + d0[k]) = w;
     }
   }
 }
@@ -470,8 +480,9 @@ __device__ __forceinline__ void attn_setup_head(const AttnParams &P, const PfWor
   H.lkv = H.hist_tokens + P.q_tokens;
   H.k_pool = P.k_pool;
   H.v_pool = P.v_pool;
-  H.k_cur = P.k_cur + (size_t)h * P.q_tokens * D;
-  H.v_cur = P.v_cur + (size_t)h * P.q_tokens * D;
+  H.k_cur = P.k_cur + (size_t)h * P.head_stride;
+  H.v_cur = P.v_cur + (size_t)h * P.head_stride;
+  H.cur_stride = P.tok_stride;
   H.slots = (const __attribute__((address_space(4))) int32_t *)(P.sel_slots + (size_t)h * P.max_sel);
   H.lrow = tid / CPR;
   H.lchunk = tid % CPR;
@@ -482,12 +493,12 @@ template <int D, int NQB>
 __device__ __forceinline__ void attn_load_q(const AttnParams &P, const PfWorkItem &it, bf16x8 (&qf)[NQB][D / 16]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31, g = lane >> 5;
-  const __bf16 *qh = P.q + (size_t)it.head * P.q_tokens * D;
+  const __bf16 *qh = P.q + (size_t)it.head * P.head_stride;
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const int row = pf_min(it.q0 + (wave * NQB + qb) * 32 + l32, P.q_tokens - 1);
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) qf[qb][ks] = *(const bf16x8 *)(qh + (size_t)row * D + ks * 16 + 8 * g);
+    for (int ks = 0; ks < D / 16; ++ks) qf[qb][ks] = *(const bf16x8 *)(qh + (size_t)row * P.tok_stride + ks * 16 + 8 * g);
   }
 }
 template <int D, int NQB>
@@ -610,7 +621,7 @@ __device__ __forceinline__ int pp_copy_rows_slow(int kt, const HeadKV &H, char *
     const int th = in_chunk ? 0 : t;
     const int j = th / H.tpf;
     const size_t e_hist = ((size_t)pf_max(H.slots[j], 0) * H.tpf + (th - j * H.tpf)) * D;
-    const size_t e = in_chunk ? (size_t)(t - H.hist_tokens) * D : e_hist;
+    const size_t e = in_chunk ? (size_t)(t - H.hist_tokens) * H.cur_stride : e_hist;
     const char *b = (const char *)((in_chunk ? (IS_V ? H.v_cur : H.k_cur) : (IS_V ? H.v_pool : H.k_pool)) + e);
     const unsigned off = (unsigned)((((lane >> 2) ^ pp_swz(IS_V, row)) << 4) | ((lane & 3) << 2));
     __builtin_amdgcn_global_load_lds((gptr_t)(b + off), (lptr_t)(stage + row * 256), 4, 0, 0);
@@ -707,12 +718,28 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
       else __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofV, wrow_bytes, 1024, 0);
     }
   };
+  // The same for a chunk tile whose token rows are cur_stride elements apart (the model's [tokens][heads][D]
+  // layout): the lane's row is part of its vector offset, the wave's first row and the second group are scalar
+  // offsets, and the second group's LDS destination moves by hand.
+  const unsigned row_b = (unsigned)(H.cur_stride * 2);         // bytes between chunk token rows (< 2^25, checked on the host)
+  const unsigned sofK0 = (unsigned)(((vofK0 & 0xffu) + (lane >> 4) * row_b)), sofK1 = (unsigned)(((vofK1 & 0xffu) + (lane >> 4) * row_b));
+  const unsigned sofV = (unsigned)(((vofV & 0xffu) + (lane >> 4) * row_b));
+  auto copy_group_strided = [&](const TileSrc &src, int snk, int snv, int h) {
+    constexpr unsigned RSRC_FLAGS = 0x00020000u;
+    const unsigned soff = (unsigned)(wave * 8 + 4 * (h & 1)) * row_b;
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)(h < 2 ? src.kb : src.vb), 0, (int)(PF_BK * row_b), RSRC_FLAGS);
+    lptr_t dst = h < 2 ? (lptr_t)(&sK[snk][wrow_bytes + (h & 1) * 1024]) : (lptr_t)(&sV[snv][wrow_bytes + (h & 1) * 1024]);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, h == 0 ? sofK0 : h == 1 ? sofK1 : sofV, soff, 0, 0);
+  };
   // whole tile at once (prologue, and tiles that cross a frame border or hold the ragged end)
   auto copy_tile_now = [&](int kt, const TilePos &tp, int snk, int snv) -> int {
     const TileSrc src = tile_src(kt, tp, H, D);
     if (src.simple) {
 #pragma unroll
-      for (int h = 0; h < 4; ++h) copy_group(src, snk, snv, h);
+      for (int h = 0; h < 4; ++h) {
+        if (src.strided) copy_group_strided(src, snk, snv, h);
+        else copy_group(src, snk, snv, h);
+      }
       return 4;
     }
     pp_copy_rows_slow<false>(kt, H, sK[snk], wave, lane);
@@ -784,14 +811,15 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   nsrc.simple = false;
   int ncopy_kt = -1;                                           // tile planned for the next copy, -1: none
   int run_left = 0;                                            // tiles after the planned one that continue its source run
+  long long run_step = 0;                                      // elements from one tile of the run to the next
   auto plan_copy = [&](int kt_target) {
     if (__builtin_expect(run_left > 0, 1)) {
       // common case: the tile follows a contiguous tile of the same frame (or of the chunk), is itself whole and
       // inside it, and belongs to this work item: both sources move on by one tile, no slot lookup
       --run_left;
       pos.r += PF_BK;
-      nsrc.kb += PF_BK * D;
-      nsrc.vb += PF_BK * D;
+      nsrc.kb += run_step;
+      nsrc.vb += run_step;
       ncopy_kt = kt_target;
       return;
     }
@@ -803,6 +831,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
       if (nsrc.simple) {
         const int room = pos.j < H.n_sel ? H.tpf - pos.r : H.lkv - kt_target * PF_BK;   // keys from the tile's first row to the run's end
         run_left = pf_min(room / PF_BK - 1, it.kt1 - 1 - kt_target);
+        run_step = (long long)PF_BK * (pos.j < H.n_sel ? D : H.cur_stride);
       }
     }
   };
@@ -841,8 +870,13 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
       const int snk = (sk_ + 3) & (PP_KSTAGES - 1);
       const int snv = sv_ >= 2 ? sv_ - 2 : sv_ + PP_VSTAGES - 2;
       if (__builtin_expect(nsrc.simple, 1)) {
+        if (__builtin_expect(nsrc.strided, 0)) {
 #pragma unroll
-        for (int h = 0; h < 4; ++h) copy_group(nsrc, snk, snv, h);
+          for (int h = 0; h < 4; ++h) copy_group_strided(nsrc, snk, snv, h);
+        } else {
+#pragma unroll
+          for (int h = 0; h < 4; ++h) copy_group(nsrc, snk, snv, h);
+        }
         n_last = 4;
       } else {
         pp_copy_rows_slow<false>(ncopy_kt, H, sK[snk], wave, lane);
@@ -923,11 +957,22 @@ static int launch_attn(const AttnParams &P, int head_dim, int variant, int n_blo
   return hipGetLastError() == hipSuccess ? PF_OK : PF_ERR_HIP;
 }
 
-extern "C" int pf_ragged_attn_fwd(const pf_pool *pool, const pf_index *index, const void *q, const void *k_cur,
-                                  const void *v_cur, void *out, int q_tokens, float softmax_scale,
-                                  void *workspace, size_t workspace_bytes, void *stream) {
+// Strides of the chunk tensors are usable when rows are 16-byte aligned, at least head_dim long, and the
+// (head, token) rows do not overlap: heads outermost or tokens outermost.
+bool pf_chunk_layout_ok(const pf_chunk_layout *lay, int n_heads, int tokens, int head_dim) {
+  if (!lay) return true;
+  const long long ts = lay->token_stride, hs = lay->head_stride;
+  if (ts < head_dim || hs < head_dim || (ts & 7) || (hs & 7)) return false;
+  if (ts >= (1ll << 24) || hs > (1ll << 40)) return false;   // 64 rows of a tile stay inside a 32-bit byte offset
+  return hs >= (long long)tokens * ts || ts >= (long long)n_heads * hs;
+}
+
+static int attn_fwd_impl(const pf_pool *pool, const pf_index *index, const void *q, const void *k_cur,
+                         const void *v_cur, void *out, int q_tokens, float softmax_scale, void *workspace,
+                         size_t workspace_bytes, const pf_chunk_layout *layout, void *stream) {
   const int rc = pf_validate_pool(pool);
   if (rc != PF_OK) return rc;
+  if (q_tokens >= 1 && !pf_chunk_layout_ok(layout, pool->n_heads, q_tokens, pool->head_dim)) return PF_ERR_INVALID_ARG;
   if (!index || !q || !k_cur || !v_cur || !out || q_tokens < 1) return PF_ERR_INVALID_ARG;
   if ((((uintptr_t)q) | ((uintptr_t)k_cur) | ((uintptr_t)v_cur) | ((uintptr_t)out) | ((uintptr_t)workspace)) & 15u)
     return PF_ERR_INVALID_ARG;
@@ -958,8 +1003,24 @@ extern "C" int pf_ragged_attn_fwd(const pf_pool *pool, const pf_index *index, co
   P.tpf = pool->tokens_per_frame;
   P.q_tokens = q_tokens;
   P.n_qt = n_qt;
+  P.tok_stride = layout ? layout->token_stride : pool->head_dim;
+  P.head_stride = layout ? layout->head_stride : (long long)q_tokens * pool->head_dim;
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)pool->head_dim);
   P.scale_log2 = scale * 1.4426950408889634f;
   hipStream_t st = (hipStream_t)stream;
   return launch_attn(P, pool->head_dim, index->variant, index->n_blocks, st);
+}
+
+extern "C" int pf_ragged_attn_fwd(const pf_pool *pool, const pf_index *index, const void *q, const void *k_cur,
+                                  const void *v_cur, void *out, int q_tokens, float softmax_scale,
+                                  void *workspace, size_t workspace_bytes, void *stream) {
+  return attn_fwd_impl(pool, index, q, k_cur, v_cur, out, q_tokens, softmax_scale, workspace, workspace_bytes, nullptr, stream);
+}
+
+extern "C" int pf_ragged_attn_fwd_strided(const pf_pool *pool, const pf_index *index, const void *q, const void *k_cur,
+                                          const void *v_cur, void *out, int q_tokens, float softmax_scale,
+                                          void *workspace, size_t workspace_bytes, const pf_chunk_layout *layout,
+                                          void *stream) {
+  if (!layout) return PF_ERR_INVALID_ARG;
+  return attn_fwd_impl(pool, index, q, k_cur, v_cur, out, q_tokens, softmax_scale, workspace, workspace_bytes, layout, stream);
 }

@@ -37,6 +37,10 @@ struct PoolAppendParams {
   int32_t *n_frames, *frame_ids, *T_dev, *sync;
   float *frame_score;
   int T, n_new, frame_units, blocks_per_head;
+  // new frames: 16-byte units per row (head_dim / 8), and strides in units between tokens and between heads
+  // (packed [heads][n_new][tokens][D]: row_units and n_new * frame_units)
+  int row_units;
+  long long new_tok_units, new_head_units;
 };
 
 // Is candidate frame `f` (an intermediate frame of head p at history length T) kept by the type rule?
@@ -147,7 +151,8 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
 
   // ---- payload: this workgroup owns 16-byte units [u0, u0+POOL_CHUNK_UNITS) of every frame ----
   uint4 *pool = (is_v ? P.v_pool : P.k_pool) + (size_t)base * P.frame_units;
-  const uint4 *fresh = (is_v ? P.v_new : P.k_new) + (size_t)h * P.n_new * P.frame_units;
+  const uint4 *fresh = (is_v ? P.v_new : P.k_new) + (size_t)h * P.new_head_units;
+  const int tpf = P.frame_units / P.row_units;
   const int u0 = blockIdx.x * POOL_CHUNK_UNITS + tid;
   for (int m0 = 0; m0 < n_moves; m0 += POOL_MOVE_BATCH) {
     uint4 r[POOL_MOVE_BATCH][POOL_UNITS_PER_THREAD];
@@ -155,11 +160,16 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
     for (int b = 0; b < POOL_MOVE_BATCH; ++b) {
       if (m0 + b >= n_moves) break;
       const int src = s_move_src[m0 + b];
-      const uint4 *sp = src >= 0 ? pool + (size_t)src * P.frame_units : fresh + (size_t)(-src - 1) * P.frame_units;
 #pragma unroll
       for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u) {
         const int unit = u0 + u * POOL_THREADS;
-        if (unit < P.frame_units) r[b][u] = sp[unit];
+        if (unit >= P.frame_units) continue;
+        if (src >= 0) {
+          r[b][u] = pool[(size_t)src * P.frame_units + unit];
+        } else {                                   // a new frame: token rows may be strided
+          const int tok = unit / P.row_units, c = unit - tok * P.row_units;
+          r[b][u] = fresh[((size_t)(-src - 1) * tpf + tok) * P.new_tok_units + c];
+        }
       }
     }
 #pragma unroll
@@ -268,11 +278,13 @@ extern "C" int pf_pool_reset(pf_pool *pool, void *stream) {
   return PF_OK;
 }
 
-extern "C" int pf_cache_append(pf_pool *pool, const void *k_new, const void *v_new, int n_new,
-                               const float *scores, void *stream) {
+static int cache_append_impl(pf_pool *pool, const void *k_new, const void *v_new, int n_new, const float *scores,
+                             const pf_chunk_layout *layout, void *stream) {
   const int rc = pf_validate_pool(pool);
   if (rc != PF_OK) return rc;
   if (!k_new || !v_new || n_new < 1) return PF_ERR_INVALID_ARG;
+  if (n_new <= (1 << 20) && !pf_chunk_layout_ok(layout, pool->n_heads, n_new * pool->tokens_per_frame, pool->head_dim))
+    return PF_ERR_INVALID_ARG;
   if ((((uintptr_t)k_new) & 15u) || (((uintptr_t)v_new) & 15u)) return PF_ERR_INVALID_ARG;
   if ((long long)pool->T_host + n_new > (1ll << 30)) return PF_ERR_INVALID_ARG;
   const int T_new = pool->T_host + n_new;
@@ -298,6 +310,9 @@ extern "C" int pf_cache_append(pf_pool *pool, const void *k_new, const void *v_n
   P.n_new = n_new;
   P.frame_units = pool->tokens_per_frame * pool->head_dim / 8;   // bf16: 8 elements per 16 bytes
   P.blocks_per_head = pf_ceil_div(P.frame_units, POOL_CHUNK_UNITS);
+  P.row_units = pool->head_dim / 8;
+  P.new_tok_units = layout ? layout->token_stride / 8 : P.row_units;
+  P.new_head_units = layout ? layout->head_stride / 8 : (long long)n_new * P.frame_units;
   hipLaunchKernelGGL(pf_pool_append_kernel, dim3(P.blocks_per_head, pool->n_heads, 2), dim3(POOL_THREADS), 0,
                      (hipStream_t)stream, P);
   PF_HIP_CHECK(hipGetLastError());
@@ -323,4 +338,15 @@ extern "C" int pf_cache_append(pf_pool *pool, const void *k_new, const void *v_n
   }
   pool->T_host = T_new;
   return PF_OK;
+}
+
+extern "C" int pf_cache_append(pf_pool *pool, const void *k_new, const void *v_new, int n_new,
+                               const float *scores, void *stream) {
+  return cache_append_impl(pool, k_new, v_new, n_new, scores, nullptr, stream);
+}
+
+extern "C" int pf_cache_append_strided(pf_pool *pool, const void *k_new, const void *v_new, int n_new,
+                                       const float *scores, const pf_chunk_layout *layout, void *stream) {
+  if (!layout) return PF_ERR_INVALID_ARG;
+  return cache_append_impl(pool, k_new, v_new, n_new, scores, layout, stream);
 }

@@ -72,8 +72,17 @@ def compare_attention(out_g, want, rows=None, label=""):
 
 
 def run_case(pols, tpf, D, chunks, Lq, seed, with_scores=True, q_gain=1.0, seg_tiles=0, rows=None,
-             check_every_append=True, scale=0.0, device="cuda:0", label="case"):
-    """Full path on both sides.  Returns (worst max-abs, worst relative L2) of the attention output."""
+             check_every_append=True, scale=0.0, device="cuda:0", label="case", layout="packed"):
+    """Full path on both sides.  Returns (worst max-abs, worst relative L2) of the attention output.
+    layout="model": the GPU side holds the new frames and the chunk tensors as [tokens][heads][D] and goes
+    through the strided entry points (same values, so the oracle side does not change)."""
+    model = layout == "model"
+
+    def as_model(t):              # [H, ..., D] on the CPU -> heads-first view of a [tokens][H][D] device tensor
+        flat = t.reshape(t.shape[0], -1, t.shape[-1]).to(device)
+        return flat.permute(1, 0, 2).contiguous().permute(1, 0, 2).reshape(t.shape) if t.dim() == 3 else \
+            flat.permute(1, 0, 2).contiguous().permute(1, 0, 2).unflatten(1, tuple(t.shape[1:-1]))
+
     H = len(pols)
     pool_o = PoolOracle(pols, tpf, D)
     pool_g = B.Pool(pols, tpf, D, device=device)
@@ -84,7 +93,10 @@ def run_case(pols, tpf, D, chunks, Lq, seed, with_scores=True, q_gain=1.0, seg_t
         v_new = synth.randn_bf16((H, n_new, tpf, D), seed * 1000 + 2 * ci + 1)
         sc = synth.frame_scores(H, n_new, seed * 1000 + 500 + ci) if with_scores else None
         pool_o.append(synth.bits(k_new), synth.bits(v_new), None if sc is None else sc.numpy())
-        B.pf_cache_append(pool_g, k_new.to(device), v_new.to(device), None if sc is None else sc.to(device))
+        if model:
+            B.pf_cache_append_strided(pool_g, as_model(k_new), as_model(v_new), None if sc is None else sc.to(device))
+        else:
+            B.pf_cache_append(pool_g, k_new.to(device), v_new.to(device), None if sc is None else sc.to(device))
         T += n_new
         if check_every_append or ci == len(chunks) - 1:
             check_pool(pool_g, pool_o)
@@ -97,18 +109,23 @@ def run_case(pols, tpf, D, chunks, Lq, seed, with_scores=True, q_gain=1.0, seg_t
     k_cur = synth.randn_bf16((H, Lq, D), seed * 1000 + 901)
     v_cur = synth.randn_bf16((H, Lq, D), seed * 1000 + 902)
     out = torch.full((H, Lq, D), float("nan"), dtype=torch.bfloat16, device=device)
+    attn = B.pf_ragged_attn_fwd
+    qg, kg, vg = q.to(device), k_cur.to(device), v_cur.to(device)
+    if model:
+        attn = B.pf_ragged_attn_fwd_strided
+        qg, kg, vg, out = as_model(q), as_model(k_cur), as_model(v_cur), as_model(out.cpu())
     ws = torch.empty(B.pf_attn_workspace_bytes(pool_g, Lq) if seg_tiles == 0 else (1 << 28), dtype=torch.uint8,
                      device=device)
-    B.pf_ragged_attn_fwd(pool_g, index, q.to(device), k_cur.to(device), v_cur.to(device), out, ws, softmax_scale=scale)
+    attn(pool_g, index, qg, kg, vg, out, ws, softmax_scale=scale)
     torch.cuda.synchronize()
     want = oracle_attention(pool_o, sel_count, sel_frames, q, k_cur, v_cur, rows=rows,
                             scale=None if scale == 0.0 else scale)
     res = compare_attention(out, want, rows=rows, label=label)
     # a second launch on the same index must give the same bits (arrival counters reset themselves)
-    out2 = torch.full_like(out, float("nan"))
-    B.pf_ragged_attn_fwd(pool_g, index, q.to(device), k_cur.to(device), v_cur.to(device), out2, ws, softmax_scale=scale)
+    out2 = torch.full_like(out, float("nan"))           # keeps the strides
+    attn(pool_g, index, qg, kg, vg, out2, ws, softmax_scale=scale)
     torch.cuda.synchronize()
-    assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), "%s: second launch differs" % label
+    assert torch.equal(out.contiguous().view(torch.int16), out2.contiguous().view(torch.int16)), "%s: second launch differs" % label
     return res
 
 

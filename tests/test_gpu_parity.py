@@ -147,21 +147,27 @@ def test_streaming_pool_and_index_at_model_frame_size():
             G.check_index(index, pool_o)
 
 
-def _full_size(name, layer, rows_n, seed, variant_label):
+def _full_size(name, layer, rows_n, seed, variant_label, layout="packed"):
     w = synth.WORKLOADS[name]
     pols = synth.policies(name, layer=layer)
     Lq = w.chunk_frames * w.tokens_per_frame
     chunks = [w.chunk_frames] * (w.history_frames // w.chunk_frames)
     rows = G.sample_rows(Lq, rows_n, seed, extra=(1559, 1560, 3119, 3120))
     a, r = G.run_case(pols, w.tokens_per_frame, w.head_dim, chunks, Lq, seed=seed, rows=rows,
-                      check_every_append=False, label=name)
-    print("%s %s sampled rows: max-abs %.2e rel %.2e" % (name, variant_label, a, r))
+                      check_every_append=False, label=name, layout=layout)
+    print("%s %s %s sampled rows: max-abs %.2e rel %.2e" % (name, variant_label, layout, a, r))
 
 
 def test_c2_one_layer_sampled_rows(variant):
     """One layer at model shape (12 heads, 4680-token chunk, 18 history frames) in the bench's launch
     configuration; 64 sampled query rows per head against the oracle."""
     _full_size("c2_layer", 0, 64, 21, variant)
+
+
+def test_c2_one_layer_model_layout_sampled_rows(variant):
+    """The same layer with the chunk tensors and the appended frames held as [tokens][heads][head_dim]
+    (strided entry points; whole chunk tiles take the strided fast path of each kernel)."""
+    _full_size("c2_layer", 0, 48, 24, variant, layout="model")
 
 
 def test_c3_layer_sampled_rows():
@@ -247,3 +253,108 @@ def test_index_and_attention_replay_from_a_hip_graph():
     graph.replay()
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int16), eager2.view(torch.int16)) and not torch.equal(eager, eager2)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_model_layout_strided_chunk_tensors(variant, D):
+    """The model's [tokens][heads][head_dim] activations go through the strided entry points without a permute:
+    the pool they fill and the attention output are bit-identical to the packed entry points on the same data
+    (which are checked against the oracle), and the output also meets the oracle's tolerance directly."""
+    dev = "cuda:0"
+    pols = _mixed(14)
+    tpf, Lq, H = 40, 100, len(pols)
+    chunks = [3, 2, 4, 1, 4]
+    pool_p, pool_s = B.Pool(pols, tpf, D, device=dev), B.Pool(pols, tpf, D, device=dev)
+    from oracle.pool import PoolOracle
+    pool_o = PoolOracle(pols, tpf, D)
+    B.pf_pool_reset(pool_p)
+    B.pf_pool_reset(pool_s)
+    for ci, n_new in enumerate(chunks):
+        # model layout: [n_new * tpf tokens][heads][D], padded with a few unused heads so that strides differ from sizes
+        km = synth.randn_bf16((n_new * tpf, H + 2, D), 300 + 2 * ci).to(dev)
+        vm = synth.randn_bf16((n_new * tpf, H + 2, D), 301 + 2 * ci).to(dev)
+        sc = synth.frame_scores(H, n_new, 350 + ci)
+        kv = km[:, :H].permute(1, 0, 2).unflatten(1, (n_new, tpf))       # view: [H, n_new, tpf, D]
+        vv = vm[:, :H].permute(1, 0, 2).unflatten(1, (n_new, tpf))
+        assert not kv.is_contiguous()
+        B.pf_cache_append_strided(pool_s, kv, vv, sc.to(dev))
+        B.pf_cache_append(pool_p, kv.contiguous(), vv.contiguous(), sc.to(dev))
+        pool_o.append(synth.bits(kv.contiguous().cpu()), synth.bits(vv.contiguous().cpu()), sc.numpy())
+        G.check_pool(pool_s, pool_o)
+    assert torch.equal(pool_s.k_pool.view(torch.int16), pool_p.k_pool.view(torch.int16))
+    assert torch.equal(pool_s.v_pool.view(torch.int16), pool_p.v_pool.view(torch.int16))
+    index = B.Index(pool_s, Lq, seg_tiles=16)
+    B.pf_build_index(pool_s, index, Lq)
+    sel_count, sel_frames = G.check_index(index, pool_o)
+    index_p = B.Index(pool_p, Lq, seg_tiles=16)
+    B.pf_build_index(pool_p, index_p, Lq)
+    qm, kcm, vcm = [synth.randn_bf16((Lq, H + 1, D), 380 + i).to(dev) for i in range(3)]
+    om = torch.full((Lq, H + 1, D), float("nan"), dtype=torch.bfloat16, device=dev)
+    view = lambda t: t[:, :H].permute(1, 0, 2)                            # [H, Lq, D], token stride (H+1)*D
+    ws = torch.empty(1 << 26, dtype=torch.uint8, device=dev)
+    B.pf_ragged_attn_fwd_strided(pool_s, index, view(qm), view(kcm), view(vcm), view(om), ws)
+    out_p = torch.empty((H, Lq, D), dtype=torch.bfloat16, device=dev)
+    B.pf_ragged_attn_fwd(pool_p, index_p, view(qm).contiguous(), view(kcm).contiguous(), view(vcm).contiguous(), out_p, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(view(om).contiguous().view(torch.int16), out_p.view(torch.int16))
+    assert torch.isnan(om[:, H]).all(), "the strided output wrote outside its rows"
+    want = G.oracle_attention(pool_o, sel_count, sel_frames, view(qm).cpu(), view(kcm).cpu(), view(vcm).cpu())
+    a, r = G.compare_attention(view(om).contiguous(), want, label="strided")
+    print("strided D=%d max-abs %.2e rel %.2e" % (D, a, r))
+
+
+def test_whole_chunk_from_a_hip_graph():
+    """One chunk of a rollout in the model's layout -- two denoising passes of attention, the write-back of the
+    chunk's keys and values from where attention read them, and the next chunk's index -- captured into one HIP
+    graph gives the same pool, index and outputs as the eager calls."""
+    dev = "cuda:0"
+    pols = _mixed(16)
+    tpf, D, n_new, H = 48, 128, 3, len(pols)
+    Lq = n_new * tpf
+
+    def fresh_state():
+        pool = B.Pool(pols, tpf, D, device=dev)
+        B.pf_pool_reset(pool)
+        for ci in range(3):
+            B.pf_cache_append(pool, synth.randn_bf16((H, 3, tpf, D), 400 + ci).to(dev),
+                              synth.randn_bf16((H, 3, tpf, D), 410 + ci).to(dev), synth.frame_scores(H, 3, 420 + ci).to(dev))
+        index = B.Index(pool, Lq, seg_tiles=16)
+        B.pf_build_index(pool, index, Lq)
+        return pool, index
+
+    qm, kcm, vcm = [synth.randn_bf16((Lq, H, D), 430 + i).to(dev) for i in range(3)]
+    sc = synth.frame_scores(H, n_new, 440).to(dev)
+    ws = torch.empty(1 << 26, dtype=torch.uint8, device=dev)
+    view = lambda t: t.permute(1, 0, 2)
+
+    def chunk(pool, index, outs):
+        for o in outs:
+            B.pf_ragged_attn_fwd_strided(pool, index, view(qm), view(kcm), view(vcm), view(o), ws)
+        B.pf_cache_append_strided(pool, view(kcm).unflatten(1, (n_new, tpf)), view(vcm).unflatten(1, (n_new, tpf)), sc)
+        B.pf_build_index(pool, index, Lq)
+
+    pool_e, index_e = fresh_state()
+    outs_e = [torch.zeros((Lq, H, D), dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    chunk(pool_e, index_e, outs_e)
+    torch.cuda.synchronize()
+
+    pool_g, index_g = fresh_state()
+    outs_g = [torch.zeros((Lq, H, D), dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            chunk(pool_g, index_g, outs_g)                        # recorded only: the pool is still at 9 frames
+    torch.cuda.synchronize()
+    assert int(pool_g.T_dev.item()) == 9 and pool_g.T == 12      # host mirror advanced at capture, device not yet
+    graph.replay()
+    torch.cuda.synchronize()
+    for a, b in zip(outs_e, outs_g):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    for name in ("n_frames", "frame_ids", "frame_score", "k_pool", "v_pool", "T_dev"):
+        ta, tb = getattr(pool_e, name), getattr(pool_g, name)
+        assert torch.equal(ta.view(torch.int16) if ta.dtype == torch.bfloat16 else ta, tb.view(torch.int16) if tb.dtype == torch.bfloat16 else tb), name
+    for name in ("sel_count", "sel_frames", "sel_slots", "cu_seqlens"):
+        assert torch.equal(getattr(index_e, name), getattr(index_g, name)), name

@@ -119,3 +119,24 @@ def test_argument_validation_without_a_device():
     assert lib.pf_ragged_attn_fwd(ctypes.byref(pool), ctypes.byref(idx), fake, fake, fake, fake, 32, 0.0, null, 0,
                                   null) == B.PF_ERR_INVALID_ARG
     assert B.lib().pf_status_string(B.PF_ERR_CAPACITY) == b"capacity exceeded"
+
+
+def test_chunk_layout_validation_without_a_device():
+    """Strided entry points: stride checks happen on the host, before any device access."""
+    lib = B.lib()
+    pols = [synth.anchor_all(4), synth.veil(1, 2)]
+    pool = _fake_pool(pols)                                   # head_dim 64, 16 tokens per frame
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    idx = B.pf_index(8, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 20, 48, 0, 8, 0, 0, 0)
+    lay = lambda ts, hs: ctypes.byref(B.pf_chunk_layout(ts, hs))
+    bad = [(0, 64), (60, 64 * 48), (64, 60), (32, 64 * 48), (128, 100), (128, 64 * 8)]   # short, unaligned, overlapping rows
+    for ts, hs in bad:
+        assert lib.pf_ragged_attn_fwd_strided(ctypes.byref(pool), ctypes.byref(idx), fake, fake, fake, fake, 48, 0.0, null, 0,
+                                              lay(ts, hs), null) == B.PF_ERR_INVALID_ARG, (ts, hs)
+        assert lib.pf_cache_append_strided(ctypes.byref(pool), fake, fake, 3, null, lay(ts, hs), null) == B.PF_ERR_INVALID_ARG
+    assert lib.pf_ragged_attn_fwd_strided(ctypes.byref(pool), ctypes.byref(idx), fake, fake, fake, fake, 48, 0.0, null, 0,
+                                          None, null) == B.PF_ERR_INVALID_ARG
+    assert lib.pf_cache_append_strided(ctypes.byref(pool), fake, fake, 3, null, None, null) == B.PF_ERR_INVALID_ARG
+    # a good layout passes the stride check and fails later, on capacity (5 frames into 4 slots): nothing was launched
+    assert lib.pf_cache_append_strided(ctypes.byref(pool), fake, fake, 5, null, lay(2 * 64, 64), null) == B.PF_ERR_CAPACITY
+    assert pool.T_host == 0
