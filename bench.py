@@ -187,7 +187,8 @@ def main():
         "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "roofline": {"kernel": "pf_attn_pp_kernel" if int(layers[0][1].c.variant) == 1 else "pf_attn_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None, "avg_launch_ms": round(attn_ms_avg, 4),
+                     "traffic": profiled_traffic(w.name, int(layers[0][1].c.variant), args.layout),
+                     "avg_launch_ms": round(attn_ms_avg, 4),
                      "flop_per_launch": flops_per_launch, "launches_timed": len(attn_ms)},
         "pool_append": {"kernel": "pf_pool_append_kernel", "bound": "hbm",
                         "what": "the append of %d frames that brings each layer's pool to %d frames "
@@ -224,6 +225,22 @@ def main():
                                             "%.1f s incl. assembling each head's keys)" % (H, len(rows), cpu_flops / 1e9, cpu_s),
                                   "parity_max_abs": float(worst_abs), "parity_rel_l2": float(worst_rel)}
     print(json.dumps(result))
+
+
+def profiled_traffic(workload, variant, layout):
+    """HBM bytes per attention launch from the committed rocprofv3 counter summary of this command (FETCH_SIZE and
+    WRITE_SIZE passes, scaled by the copy probe); counters cannot be read inside a timed run.  None when the
+    summary does not cover this workload / kernel."""
+    if workload != "c3_step" or variant != 1 or layout != "packed":
+        return None
+    path = os.path.join(ROOT, "profiles", "pf_attn_pp_kernel_c3_step.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def stream_bench(args, B, synth, dev):
