@@ -140,3 +140,31 @@ def frame_scores(n_heads, n_frames, seed, device="cpu"):
 def bits(t):
     """bfloat16 tensor -> numpy uint16 bit patterns (host copy)."""
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view("uint16")
+
+
+# ---- historical attention sequences for the offline head classification (Sec. 4.1) --------------------
+# Kinds of synthetic sequence (what the paper's observations describe, plus its two failure cases):
+#   0 broadly positive scores (Anchor-like)        1 oscillation of period ~6 around zero (Wave-like)
+#   2 suppressed history (Veil-like)               3 one-sided oscillation ("pseudo-periodic", positive bias)
+#   4 slow drift around zero, no short period      5 the same with a negative mean
+LOGIT_KINDS = 6
+
+
+def head_logits(n_prompts, n_heads, n_hist, seed, wave_period=6.0):
+    """Seeded float32 sequences [n_prompts, n_heads, n_hist] and the kind of every head [n_heads].  The kind is a
+    property of the head; prompts differ by noise, phase and a small period jitter."""
+    g = _cpu_gen(seed)
+    kinds = torch.randint(0, LOGIT_KINDS, (n_heads,), generator=g)
+    t = torch.arange(n_hist, dtype=torch.float64)[None, None, :]
+    noise = torch.randn((n_prompts, n_heads, n_hist), generator=g, dtype=torch.float64)
+    phase = torch.rand((n_prompts, n_heads, 1), generator=g, dtype=torch.float64) * 6.283185307179586
+    jitter = 1.0 + 0.04 * (torch.rand((n_prompts, n_heads, 1), generator=g, dtype=torch.float64) - 0.5)
+    osc = torch.sin(6.283185307179586 * t / (wave_period * jitter) + phase)
+    slow = torch.sin(6.283185307179586 * t / (n_hist * 0.45) + phase)
+    k = kinds[None, :, None]
+    x = torch.where(k == 0, 1.6 + 0.9 * noise,
+        torch.where(k == 1, 1.5 * osc + 0.35 * noise,
+        torch.where(k == 2, -1.6 + 0.9 * noise,
+        torch.where(k == 3, 2.2 + 1.2 * osc + 0.3 * noise,
+        torch.where(k == 4, 0.25 + 1.4 * slow + 0.06 * noise, -0.25 + 1.4 * slow + 0.06 * noise)))))
+    return x.to(torch.float32), kinds
