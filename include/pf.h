@@ -240,6 +240,28 @@ int pf_ragged_attn_fwd_strided(const pf_pool *pool, const pf_index *index,
                                void *workspace, size_t workspace_bytes,
                                const pf_chunk_layout *layout, void *stream);
 
+/* ---- before the hot path: which head gets which policy -------------------- */
+
+/*
+ * Offline tri-pattern head classification (Sec. 4.1).  For every sampled prompt p and
+ * head h, logits[p][h][t] is the historical attention sequence a(t): the pre-softmax
+ * score of the newest frame towards history frame t, t = 0 .. n_hist-1.  Per sequence:
+ *   r_pos = fraction of positive scores; r_pos >= alpha -> PF_ANCHOR, 1 - r_pos >= alpha -> PF_VEIL;
+ *   otherwise the dominant period P of the sequence (first-order difference, mean removal,
+ *   Hann window, real spectrum without the zero-frequency bin, harmonic folding with weights
+ *   1/j over 4 harmonics, P = length / bin; appendix on the FFT analysis): P < beta -> PF_WAVE;
+ *   otherwise mean(a) > 0 -> PF_ANCHOR, else PF_VEIL.
+ * head_type[h] is the majority vote over the prompts (equal counts: the smaller code).
+ *   logits         dev [n_prompts][n_heads][n_hist] float, n_hist <= 1024
+ *   head_type      dev [n_heads] int32 (out)
+ *   prompt_type    dev [n_prompts][n_heads] int32 (out, also the vote's input)
+ *   prompt_period  dev [n_prompts][n_heads] double (out) or NULL: P, +inf where it was not computed
+ * The paper's thresholds are alpha = 0.8, beta = 6.4.  fp64 arithmetic throughout.
+ */
+int pf_classify_heads(const float *logits, int n_prompts, int n_heads, int n_hist,
+                      double alpha, double beta, int32_t *head_type, int32_t *prompt_type,
+                      double *prompt_period, void *stream);
+
 /* Human-readable text for a status code (static storage). */
 const char *pf_status_string(int status);
 

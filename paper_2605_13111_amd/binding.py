@@ -16,7 +16,7 @@ PF_OK, PF_ERR_INVALID_ARG, PF_ERR_CAPACITY, PF_ERR_UNSUPPORTED, PF_ERR_HIP = 0, 
 
 EXPORTS = ["pf_index_work_bytes", "pf_attn_workspace_bytes", "pf_selected_count", "pf_retained_count",
            "pf_pool_reset", "pf_cache_append", "pf_cache_append_strided", "pf_build_index", "pf_ragged_attn_fwd",
-           "pf_ragged_attn_fwd_strided", "pf_status_string"]
+           "pf_ragged_attn_fwd_strided", "pf_classify_heads", "pf_status_string"]
 
 
 class pf_head_policy(ctypes.Structure):
@@ -78,6 +78,8 @@ def lib():
         L.pf_ragged_attn_fwd_strided.restype = I
         L.pf_ragged_attn_fwd_strided.argtypes = [P(pf_pool), P(pf_index), V, V, V, V, I, ctypes.c_float, V, ctypes.c_size_t,
                                                  P(pf_chunk_layout), V]
+        L.pf_classify_heads.restype = I
+        L.pf_classify_heads.argtypes = [V, I, I, I, ctypes.c_double, ctypes.c_double, V, V, V, V]
         L.pf_status_string.restype = ctypes.c_char_p
         L.pf_status_string.argtypes = [I]
         _lib = L
@@ -244,3 +246,16 @@ def pf_ragged_attn_fwd_strided(pool, index, q, k_cur, v_cur, out, workspace, sof
                                             _ptr(v_cur), _ptr(out), int(q.shape[1]), float(softmax_scale),
                                             _ptr(workspace), ws_bytes, ctypes.byref(lay), _stream(stream)),
            "pf_ragged_attn_fwd_strided")
+
+
+def pf_classify_heads(logits, alpha=0.8, beta=6.4, with_periods=True, stream=None):
+    """logits: float32 [n_prompts, n_heads, n_hist] on the GPU.  Returns (head_type [n_heads] int32,
+    prompt_type [n_prompts, n_heads] int32, prompt_period [n_prompts, n_heads] float64 or None)."""
+    assert logits.is_contiguous() and logits.dtype == torch.float32 and logits.dim() == 3
+    n_p, n_h, n_t = logits.shape
+    head_type = torch.empty(n_h, dtype=torch.int32, device=logits.device)
+    prompt_type = torch.empty((n_p, n_h), dtype=torch.int32, device=logits.device)
+    prompt_period = torch.empty((n_p, n_h), dtype=torch.float64, device=logits.device) if with_periods else None
+    _check(lib().pf_classify_heads(_ptr(logits), n_p, n_h, n_t, float(alpha), float(beta), _ptr(head_type),
+                                   _ptr(prompt_type), _ptr(prompt_period), _stream(stream)), "pf_classify_heads")
+    return head_type, prompt_type, prompt_period

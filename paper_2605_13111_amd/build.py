@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpf.so")
-SOURCES = ["pf_host.hip", "pf_pool.hip", "pf_index.hip", "pf_attn.hip"]
+SOURCES = ["pf_host.hip", "pf_pool.hip", "pf_index.hip", "pf_attn.hip", "pf_classify.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # Packed-FP32 code generation is switched off for every device translation unit.

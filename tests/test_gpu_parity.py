@@ -358,3 +358,42 @@ def test_whole_chunk_from_a_hip_graph():
         assert torch.equal(ta.view(torch.int16) if ta.dtype == torch.bfloat16 else ta, tb.view(torch.int16) if tb.dtype == torch.bfloat16 else tb), name
     for name in ("sel_count", "sel_frames", "sel_slots", "cu_seqlens"):
         assert torch.equal(getattr(index_e, name), getattr(index_g, name)), name
+
+
+def test_head_classification_matches_the_oracle():
+    """Offline tri-pattern classification (Sec. 4.1): per-prompt types, periods and the voted head types of the
+    kernel equal the oracle's exactly, on the synthetic sequences at the paper's sizes (30 x 12 heads, 69 history
+    frames) and on short, degenerate and hand-made sequences (thresholds hit exactly, tied spectral peaks)."""
+    from oracle import classify as OC
+    dev = "cuda:0"
+    logits, kinds = synth.head_logits(32, 360, 69, seed=11)
+    head, ptype, pper = B.pf_classify_heads(logits.to(dev))
+    torch.cuda.synchronize()
+    oh, ot, op = OC.classify_heads(logits.numpy())
+    assert np.array_equal(ptype.cpu().numpy(), ot)
+    assert np.array_equal(pper.cpu().numpy(), op)                       # N / k on both sides, inf where unused
+    assert np.array_equal(head.cpu().numpy(), oh)
+    assert set(np.unique(oh)) == {0, 1, 2}
+    # other thresholds, and every short length (no spectrum below 4 points)
+    for n_hist, alpha, beta in [(1, 0.8, 6.4), (2, 0.8, 6.4), (3, 0.6, 6.4), (4, 0.8, 6.4), (5, 0.9, 3.0), (7, 0.7, 4.0),
+                                (33, 0.75, 8.0), (130, 0.8, 6.4), (1024, 0.8, 6.4)]:
+        lg, _ = synth.head_logits(5, 24, n_hist, seed=100 + n_hist)
+        head, ptype, pper = B.pf_classify_heads(lg.to(dev), alpha=alpha, beta=beta)
+        torch.cuda.synchronize()
+        oh, ot, op = OC.classify_heads(lg.numpy(), alpha, beta)
+        assert np.array_equal(ptype.cpu().numpy(), ot), n_hist
+        assert np.array_equal(pper.cpu().numpy(), op), n_hist
+        assert np.array_equal(head.cpu().numpy(), oh), n_hist
+    # hand-made: sign rate exactly at the threshold, flat, alternating, two equal tones (tie -> the lower bin)
+    t = np.arange(121)
+    rows = [np.tile(np.array([1.0] * 8 + [-1.0] * 2), 13)[:121], -np.tile(np.array([1.0] * 8 + [-1.0] * 2), 13)[:121],
+            np.ones(121), np.zeros(121), np.where(t % 2 == 0, 1.0, -1.0),
+            np.sin(2 * np.pi * t / 6.0), np.sin(2 * np.pi * t / 6.0) + 2.0, np.sin(2 * np.pi * t / 40.0) - 0.05,
+            np.sin(2 * np.pi * t / 12.0) + 0.7 * np.sin(2 * np.pi * t / 6.0 + 1.1),
+            np.sin(2 * np.pi * t / 10.0) + np.sin(2 * np.pi * t / 5.0)]
+    lg = torch.tensor(np.stack(rows)[None].astype(np.float32))
+    head, ptype, pper = B.pf_classify_heads(lg.to(dev))
+    torch.cuda.synchronize()
+    oh, ot, op = OC.classify_heads(lg.numpy())
+    assert np.array_equal(ptype.cpu().numpy(), ot) and np.array_equal(pper.cpu().numpy(), op)
+    assert ot[0].tolist()[:8] == [0, 2, 0, 2, 1, 1, 0, 2]

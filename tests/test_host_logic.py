@@ -140,3 +140,18 @@ def test_chunk_layout_validation_without_a_device():
     # a good layout passes the stride check and fails later, on capacity (5 frames into 4 slots): nothing was launched
     assert lib.pf_cache_append_strided(ctypes.byref(pool), fake, fake, 5, null, lay(2 * 64, 64), null) == B.PF_ERR_CAPACITY
     assert pool.T_host == 0
+
+
+def test_classify_argument_validation_without_a_device():
+    lib = B.lib()
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    call = lambda lg, n_p, n_h, n_t, al, be, ht, pt: lib.pf_classify_heads(lg, n_p, n_h, n_t, al, be, ht, pt, null, null)
+    assert call(null, 2, 3, 10, 0.8, 6.4, fake, fake) == B.PF_ERR_INVALID_ARG
+    assert call(fake, 2, 3, 10, 0.8, 6.4, null, fake) == B.PF_ERR_INVALID_ARG
+    assert call(fake, 2, 3, 10, 0.8, 6.4, fake, null) == B.PF_ERR_INVALID_ARG
+    assert call(fake, 0, 3, 10, 0.8, 6.4, fake, fake) == B.PF_ERR_INVALID_ARG
+    assert call(fake, 2, 3, 0, 0.8, 6.4, fake, fake) == B.PF_ERR_INVALID_ARG
+    assert call(fake, 2, 3, 10, 0.0, 6.4, fake, fake) == B.PF_ERR_INVALID_ARG
+    assert call(fake, 2, 3, 10, 1.5, 6.4, fake, fake) == B.PF_ERR_INVALID_ARG
+    assert call(fake, 2, 3, 10, 0.8, -1.0, fake, fake) == B.PF_ERR_INVALID_ARG
+    assert call(fake, 2, 3, 2000, 0.8, 6.4, fake, fake) == B.PF_ERR_UNSUPPORTED
