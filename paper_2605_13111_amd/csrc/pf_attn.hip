@@ -746,11 +746,13 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     pp_copy_rows_slow<true>(kt, H, sV[snv], wave, lane);
     return 16;
   };
-  // "at most n vector-memory operations outstanding", n = the copy instructions of the newest tile (0, 4 or 16)
+  // "Everything but the copies of the last vector phase has landed": at most 4 vector-memory operations may be
+  // outstanding (a contiguous tile's copies).  When the last vector phase sent a tile row by row (16 copies, at
+  // a frame border) this also waits for 12 of those, which were sent a whole matrix phase ago; when it sent
+  // nothing, the older copies are all that is in flight.
   auto wait_copies = [&](int n) {
-    if (__builtin_expect(n == 4, 1)) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);   // a contiguous tile in flight: the common case
-    else if (n == 16) __builtin_amdgcn_s_waitcnt(0x0F70 | (16 & 15) | ((16 >> 4) << 14));
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | 4);
+    if (__builtin_expect(n == 0, 0)) __builtin_amdgcn_s_waitcnt(0x0F70);
   };
 
   // ---- prologue: tiles kt0 .. kt0+2 start travelling, then Q^T is fetched.  Vector-memory operations complete
@@ -813,7 +815,19 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   int run_left = 0;                                            // tiles after the planned one that continue its source run
   long long run_step = 0;                                      // elements from one tile of the run to the next
   auto plan_copy = [&](int kt_target) {
-    if (__builtin_expect(run_left > 0, 1)) {
+    if (__builtin_expect(run_left <= 0, 0)) {
+      ncopy_kt = -1;
+      if (kt_target < it.kt1) {
+        tile_pos_advance(pos, H.n_sel, H.tpf);
+        nsrc = tile_src(kt_target, pos, H, D);
+        ncopy_kt = kt_target;
+        if (nsrc.simple) {
+          const int room = pos.j < H.n_sel ? H.tpf - pos.r : H.lkv - kt_target * PF_BK;   // keys from the tile's first row to the run's end
+          run_left = pf_min(room / PF_BK - 1, it.kt1 - 1 - kt_target);
+          run_step = (long long)PF_BK * (pos.j < H.n_sel ? D : H.cur_stride);
+        }
+      }
+    } else {
       // common case: the tile follows a contiguous tile of the same frame (or of the chunk), is itself whole and
       // inside it, and belongs to this work item: both sources move on by one tile, no slot lookup
       --run_left;
@@ -821,18 +835,6 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
       nsrc.kb += run_step;
       nsrc.vb += run_step;
       ncopy_kt = kt_target;
-      return;
-    }
-    ncopy_kt = -1;
-    if (kt_target < it.kt1) {
-      tile_pos_advance(pos, H.n_sel, H.tpf);
-      nsrc = tile_src(kt_target, pos, H, D);
-      ncopy_kt = kt_target;
-      if (nsrc.simple) {
-        const int room = pos.j < H.n_sel ? H.tpf - pos.r : H.lkv - kt_target * PF_BK;   // keys from the tile's first row to the run's end
-        run_left = pf_min(room / PF_BK - 1, it.kt1 - 1 - kt_target);
-        run_step = (long long)PF_BK * (pos.j < H.n_sel ? D : H.cur_stride);
-      }
     }
   };
 
@@ -869,14 +871,13 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     if (__builtin_expect(ncopy_kt >= 0, 1)) {
       const int snk = (sk_ + 3) & (PP_KSTAGES - 1);
       const int snv = sv_ >= 2 ? sv_ - 2 : sv_ + PP_VSTAGES - 2;
-      if (__builtin_expect(nsrc.simple, 1)) {
-        if (__builtin_expect(nsrc.strided, 0)) {
+      if (__builtin_expect(nsrc.simple && !nsrc.strided, 1)) {
 #pragma unroll
-          for (int h = 0; h < 4; ++h) copy_group_strided(nsrc, snk, snv, h);
-        } else {
+        for (int h = 0; h < 4; ++h) copy_group(nsrc, snk, snv, h);
+        n_last = 4;
+      } else if (nsrc.simple) {
 #pragma unroll
-          for (int h = 0; h < 4; ++h) copy_group(nsrc, snk, snv, h);
-        }
+        for (int h = 0; h < 4; ++h) copy_group_strided(nsrc, snk, snv, h);
         n_last = 4;
       } else {
         pp_copy_rows_slow<false>(ncopy_kt, H, sK[snk], wave, lane);
