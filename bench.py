@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--layout", default="packed", choices=["packed", "model"],
                     help="chunk tensors per head [heads][tokens][D] (default) or as the model holds them, "
                          "[tokens][heads][D], through the strided entry point")
-    ap.add_argument("--cpu-rows", type=int, default=192, help="query rows per head of layer 0 timed on the CPU oracle")
+    ap.add_argument("--cpu-rows", type=int, default=3072, help="query rows per head of layer 0 timed on the CPU oracle")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="also run one plain device-to-device copy of this many MiB (a dispatch of known size "

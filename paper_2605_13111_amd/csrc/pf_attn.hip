@@ -127,7 +127,7 @@ __device__ __forceinline__ void attn_load_rows(u32x4 (&reg)[NP], int kt, TilePos
   const int last = H.lkv - 1 - kt * PF_BK;
   const bool in_hist = pos.j < H.n_sel;
   const bool simple = last >= PF_BK - 1 && (!in_hist || pos.r + PF_BK <= H.tpf);
-  if (simple && (in_hist || H.cur_stride == D)) {
+  if (__builtin_expect(simple && (in_hist || H.cur_stride == D), 1)) {
     const char *b = in_hist ? (const char *)(pool + ((size_t)H.slots[pos.j] * H.tpf + pos.r) * D)
                             : (const char *)(cur + (size_t)pos.r * D);
 #pragma unroll
@@ -205,7 +205,6 @@ __device__ __forceinline__ void classic_loop(const HeadKV &H, int kt0, int kt1, 
   const int k_lane = l32 * KS + 8 * g;                                           // K operand: row l32, d 8g..
   const int v_lane = (4 * g + ((lane & 15) >> 2)) * VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
   const float thr = ATT_LAZY_LOG2 / c;
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
   u32x4 kreg[NP], vreg[NP];
   TilePos pos = tile_pos_init(kt0, H.hist_tokens, H.n_sel, H.tpf);
@@ -218,7 +217,7 @@ __device__ __forceinline__ void classic_loop(const HeadKV &H, int kt0, int kt1, 
   int buf = 0;
   for (int kt = kt0; kt < kt1; ++kt) {
     const bool more = kt + 1 < kt1;
-    if (more) {
+    if (__builtin_expect(more, 1)) {
       tile_pos_advance(pos, H.n_sel, H.tpf);
       attn_load_rows<D, NP, RPP>(kreg, kt + 1, pos, H, H.k_pool, H.k_cur);
       attn_load_rows<D, NP, RPP>(vreg, kt + 1, pos, H, H.v_pool, H.v_cur);
@@ -242,7 +241,7 @@ __device__ __forceinline__ void classic_loop(const HeadKV &H, int kt0, int kt1, 
     }
     // ragged tail: keys at or beyond lkv exist only in the last tile of the head
     const int valid = H.lkv - kt * BK;
-    if (valid < BK) {
+    if (__builtin_expect(valid < BK, 0)) {
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
@@ -271,7 +270,7 @@ __device__ __forceinline__ void classic_loop(const HeadKV &H, int kt0, int kt1, 
       mx[qb] = partner_max(a);
       need = need || (mx[qb] > m_run[qb] + thr);
     }
-    if (__builtin_amdgcn_ballot_w64(need) != 0) {
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(need) != 0, 0)) {
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb) {
         const float m_new = fmaxf(m_run[qb], mx[qb]);
@@ -287,17 +286,20 @@ __device__ __forceinline__ void classic_loop(const HeadKV &H, int kt0, int kt1, 
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
       const float mc = m_run[qb] * c;
+      // row sum with plain fp32 adds: dot-product instructions share the matrix pipe and queue behind MFMAs
+      float ls0 = 0.f, ls1 = 0.f;
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
-          bf16x2 pk;
-          pk[0] = (__bf16)fast_exp2(fmaf(s[qb][kb][i], c, -mc));
-          pk[1] = (__bf16)fast_exp2(fmaf(s[qb][kb][i + 1], c, -mc));
-          l_run[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run[qb], false);   // sums the rounded weights
-          pf[qb][kb * 2 + (i >> 3)][i & 7] = pk[0];
-          pf[qb][kb * 2 + (i >> 3)][(i & 7) + 1] = pk[1];
+          const float e0 = fast_exp2(fmaf(s[qb][kb][i], c, -mc));
+          const float e1 = fast_exp2(fmaf(s[qb][kb][i + 1], c, -mc));
+          ls0 += e0;
+          ls1 += e1;
+          pf[qb][kb * 2 + (i >> 3)][i & 7] = (__bf16)e0;
+          pf[qb][kb * 2 + (i >> 3)][(i & 7) + 1] = (__bf16)e1;
         }
+      l_run[qb] += ls0 + ls1;
     }
 
     // ---- O^T += V^T P^T ----
