@@ -194,7 +194,8 @@ int pf_pool_reset(pf_pool *pool, void *stream);
  *   k_new, v_new  dev [n_heads][n_new][tokens_per_frame][head_dim], 16-byte aligned
  *   scores        dev [n_heads][n_new] float, or NULL (= 0) -- used by Anchor/TOPK
  * PF_ERR_CAPACITY if any head would hold more than its `slots` frames after
- * eviction; the pool is then untouched.  On success pool->T_host += n_new.
+ * eviction, or if a head's resident frames plus n_new exceed 1024 (the kernel's
+ * per-head tables); the pool is then untouched.  On success pool->T_host += n_new.
  */
 int pf_cache_append(pf_pool *pool, const void *k_new, const void *v_new,
                     int n_new, const float *scores, void *stream);

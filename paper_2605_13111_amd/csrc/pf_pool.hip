@@ -11,7 +11,7 @@
 constexpr int POOL_THREADS = 256;
 constexpr int POOL_UNITS_PER_THREAD = 2;                    // 16-byte units per thread per frame
 constexpr int POOL_CHUNK_UNITS = POOL_THREADS * POOL_UNITS_PER_THREAD;
-constexpr int POOL_MAX_CAND = 2048;                         // resident + new frames of one head
+constexpr int POOL_MAX_CAND = 1024;                         // resident + new frames of one head (20 KB of tables per workgroup)
 constexpr int POOL_MOVE_BATCH = 8;                          // frames in flight per thread
 
 __global__ void pf_pool_reset_kernel(int32_t *n_frames, int32_t *frame_ids, float *frame_score,
