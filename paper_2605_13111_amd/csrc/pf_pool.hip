@@ -37,9 +37,9 @@ struct PoolAppendParams {
   int32_t *n_frames, *frame_ids, *T_dev, *sync;
   float *frame_score;
   int T, n_new, frame_units, blocks_per_head;
-  // new frames: 16-byte units per row (head_dim / 8), and strides in units between tokens and between heads
-  // (packed [heads][n_new][tokens][D]: row_units and n_new * frame_units)
-  int row_units;
+  // new frames: strides in 16-byte units between tokens and between heads (packed [heads][n_new][tokens][D]:
+  // head_dim / 8 and n_new * frame_units)
+  int row_shift;                        // log2 of the units per row (head_dim 64 -> 3, 128 -> 4)
   long long new_tok_units, new_head_units;
 };
 
@@ -149,37 +149,41 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
   __syncthreads();
   const int n_kept = s_counts[0], n_moves = s_counts[1];
 
-  // ---- payload: this workgroup owns 16-byte units [u0, u0+POOL_CHUNK_UNITS) of every frame ----
+  // ---- payload: this workgroup owns 16-byte units [u0, u0+POOL_CHUNK_UNITS) of every frame.  The loads of a
+  // batch are unconditional (indices clamped, the source chosen by a select) so that all of them are in flight
+  // before the first store; only the stores are predicated. ----
   uint4 *pool = (is_v ? P.v_pool : P.k_pool) + (size_t)base * P.frame_units;
   const uint4 *fresh = (is_v ? P.v_new : P.k_new) + (size_t)h * P.new_head_units;
-  const int tpf = P.frame_units / P.row_units;
+  const long long new_frame_units = (long long)(P.frame_units >> P.row_shift) * P.new_tok_units;   // tokens per frame x token stride
   const int u0 = blockIdx.x * POOL_CHUNK_UNITS + tid;
+  bool valid[POOL_UNITS_PER_THREAD];
+  int unit_c[POOL_UNITS_PER_THREAD];
+  long long fresh_off[POOL_UNITS_PER_THREAD];
+#pragma unroll
+  for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u) {
+    const int unit = u0 + u * POOL_THREADS;
+    valid[u] = unit < P.frame_units;
+    unit_c[u] = valid[u] ? unit : 0;
+    // a new frame's token rows may be strided: unit -> (token, 16-byte piece of its row)
+    fresh_off[u] = (long long)(unit_c[u] >> P.row_shift) * P.new_tok_units + (unit_c[u] & ((1 << P.row_shift) - 1));
+  }
   for (int m0 = 0; m0 < n_moves; m0 += POOL_MOVE_BATCH) {
     uint4 r[POOL_MOVE_BATCH][POOL_UNITS_PER_THREAD];
 #pragma unroll
     for (int b = 0; b < POOL_MOVE_BATCH; ++b) {
-      if (m0 + b >= n_moves) break;
-      const int src = s_move_src[m0 + b];
+      const int src = s_move_src[pf_min(m0 + b, n_moves - 1)];
+      const uint4 *from_pool = pool + (size_t)pf_max(src, 0) * P.frame_units;
+      const uint4 *from_new = fresh + (size_t)pf_max(-src - 1, 0) * new_frame_units;
 #pragma unroll
-      for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u) {
-        const int unit = u0 + u * POOL_THREADS;
-        if (unit >= P.frame_units) continue;
-        if (src >= 0) {
-          r[b][u] = pool[(size_t)src * P.frame_units + unit];
-        } else {                                   // a new frame: token rows may be strided
-          const int tok = unit / P.row_units, c = unit - tok * P.row_units;
-          r[b][u] = fresh[((size_t)(-src - 1) * tpf + tok) * P.new_tok_units + c];
-        }
-      }
+      for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u) r[b][u] = src >= 0 ? from_pool[unit_c[u]] : from_new[fresh_off[u]];
     }
 #pragma unroll
     for (int b = 0; b < POOL_MOVE_BATCH; ++b) {
-      if (m0 + b >= n_moves) break;
-      uint4 *dp = pool + (size_t)s_move_dst[m0 + b] * P.frame_units;
+      if (m0 + b < n_moves) {
+        uint4 *dp = pool + (size_t)s_move_dst[m0 + b] * P.frame_units;
 #pragma unroll
-      for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u) {
-        const int unit = u0 + u * POOL_THREADS;
-        if (unit < P.frame_units) dp[unit] = r[b][u];
+        for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u)
+          if (valid[u]) dp[unit_c[u]] = r[b][u];
       }
     }
   }
@@ -188,7 +192,9 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
   // head has read the old tables.  Each workgroup consumed the old tables (the plan above was computed from
   // them) before it signals its arrival, and nobody reads the new tables or the payload before the kernel
   // ends, so the arrival needs no memory fence (a device-scope release here would write back the die's
-  // whole L2 once per workgroup). ----
+  // whole L2 once per workgroup).  The arrival comes after the payload on purpose: atomics and loads return
+  // in order, and the counters of all heads share one cache line, so an early arrival would hold up the
+  // loads behind a queue of atomics (measured: 59 instead of 50 us). ----
   __syncthreads();
   if (tid == 0) {
     const int arrived = atomicAdd(&P.sync[h], 1);
@@ -310,8 +316,8 @@ static int cache_append_impl(pf_pool *pool, const void *k_new, const void *v_new
   P.n_new = n_new;
   P.frame_units = pool->tokens_per_frame * pool->head_dim / 8;   // bf16: 8 elements per 16 bytes
   P.blocks_per_head = pf_ceil_div(P.frame_units, POOL_CHUNK_UNITS);
-  P.row_units = pool->head_dim / 8;
-  P.new_tok_units = layout ? layout->token_stride / 8 : P.row_units;
+  P.row_shift = pool->head_dim == 128 ? 4 : 3;
+  P.new_tok_units = layout ? layout->token_stride / 8 : (1 << P.row_shift);
   P.new_head_units = layout ? layout->head_stride / 8 : (long long)n_new * P.frame_units;
   hipLaunchKernelGGL(pf_pool_append_kernel, dim3(P.blocks_per_head, pool->n_heads, 2), dim3(POOL_THREADS), 0,
                      (hipStream_t)stream, P);
