@@ -558,13 +558,14 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void pf_attn_kernel(AttnParams P) {
 // wave of a SIMD issues the 32 MFMAs of a tile (O^T += V^T P^T of the previous tile, then S^T = K Q^T of
 // the current one) the other computes its softmax on the vector ALU.  A workgroup barrier ends every phase
 // and keeps the groups in step.
-//   phase M(u)   reads K of tile u and V of tile u-1 and ends with the wait for this wave's copies of tile u+1
-//   phase V(u)   requests the first V^T fragments of tile u for the next matrix phase, sends the copies of
-//                tile u+3 into the stages tiles u-1 (K) and u-2 (V) lived in (their last readers, both groups'
-//                M(u-1), are two barriers back), plans the copy after that, then scores of tile u -> weights
-//                (masking of the ragged tail, lazy rescaling as in the rescaling loop)
-// A wave is limited by its own instruction stream (about one instruction per 5 cycles, an MFMA ~16), and the
-// matrix phase is the longer one, so the copies and their address arithmetic sit in the vector phase.
+//   phase M(u)   reads K of tile u and V of tile u-1, requests the first V^T fragments of tile u for the next
+//                matrix phase and ends with the wait for this wave's copies of tile u+1
+//   phase V(u)   sends the copies of tile u+3 into the stages tiles u-1 (K) and u-2 (V) lived in (their last
+//                readers, both groups' M(u-1), are two barriers back), plans the copy after that, then scores of
+//                tile u -> weights (masking of the ragged tail, lazy rescaling as in the rescaling loop)
+// A wave is limited by its own instruction stream (about one instruction per 5 cycles, an MFMA ~16); where the
+// copies and their address arithmetic sit was settled by measurement (in the vector phase: +3.5 % over the
+// matrix phase, start, end or spread).
 // K/V tiles travel global -> LDS three tiles ahead (K ring of 4 stages, V ring of 5: V of a tile is read one
 // phase after its K) with 16-byte copies: one instruction
 // moves four 256-byte rows (lane i -> bytes 16*i of the 1 KB destination), a quarter of the instructions the
@@ -842,7 +843,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
 
   // ---- matrix phase: PV of the tile whose V sits in stage st_pv (its fragments 0 .. PP_RING-1 already
   // requested), QK of the tile whose K sits in stage st_qk ----
-  auto m_phase = [&](auto has_pv, auto has_qk, int st_qk, int st_pv) {
+  auto m_phase = [&](auto has_pv, auto has_qk, int st_qk, int st_pv, int st_v_next) {
     constexpr bool HAS_PV = decltype(has_pv)::value, HAS_QK = decltype(has_qk)::value;
     constexpr int FIRST = HAS_PV ? 0 : 16, LAST = HAS_QK ? 31 : 15;
     const unsigned offK = st_qk * PP_TILE_BYTES, offV = st_pv * PP_TILE_BYTES;
@@ -856,6 +857,9 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
       if constexpr (I + PP_RING <= LAST) issue_frag(IntC<I + PP_RING>(), offK, offV);
       __builtin_amdgcn_sched_barrier(0);                        // keep the hand-made order: wait, MFMA, next request
     });
+    // the first V^T fragments of the QK tile (V stage st_v_next), for the next matrix phase: requested here, at the
+    // end of the shorter of the two instruction streams
+    if constexpr (HAS_QK) static_for<0, PP_RING>([&](auto f) { issue_frag(f, 0u, (unsigned)(st_v_next * PP_TILE_BYTES)); });
     __builtin_amdgcn_s_setprio(0);
     // this wave's rows of the tile after the QK tile (sent two vector phases ago) have landed once only the
     // copies of its last vector phase are outstanding
@@ -863,10 +867,8 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     __builtin_amdgcn_s_barrier();
   };
 
-  // ---- vector phase: scores of tile kt -> weights; requests the first V^T fragments of tile kt (V stage
-  // sv) for the next matrix phase and plans that phase's copy ----
+  // ---- vector phase: copies of tile kt+3, plan of the copy after that, scores of tile kt -> weights ----
   auto v_phase = [&](int kt, int sk_, int sv_) {
-    static_for<0, PP_RING>([&](auto f) { issue_frag(f, 0u, (unsigned)(sv_ * PP_TILE_BYTES)); });
     // the copy planned one vector phase ago: tile kt+3, K into the stage tile kt-1 lived in, V into tile kt-2's
     // (their last readers, both groups' M(kt-1), are two barriers back)
     n_last = 0;
@@ -933,16 +935,16 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
 
   int sk = 0, sv = 0;                                          // K and V stage of the tile whose scores are computed
   plan_copy(it.kt0 + 3);
-  m_phase(TagF(), TagT(), 0, PP_VSTAGES - 1);                  // "the V stage before tile kt0's"
+  m_phase(TagF(), TagT(), 0, PP_VSTAGES - 1, 0);               // "the V stage before tile kt0's"
   v_phase(it.kt0, 0, 0);
   for (int kt = it.kt0 + 1; kt < it.kt1; ++kt) {
     const int sp = sv;
     sk = (sk + 1) & (PP_KSTAGES - 1);
     sv = sv + 1 == PP_VSTAGES ? 0 : sv + 1;
-    m_phase(TagT(), TagT(), sk, sp);
+    m_phase(TagT(), TagT(), sk, sp, sv);
     v_phase(kt, sk, sv);
   }
-  m_phase(TagT(), TagF(), 0, sv);
+  m_phase(TagT(), TagF(), 0, sv, 0);
   if (grp == 0) __builtin_amdgcn_s_barrier();                  // group 0 waits for group 1's last phase
   __syncthreads();
   attn_epilogue<D, 1, PP_WAVES>(P, it, o, m_run, l_run, (float *)&sK[0][0], &sFlag);
