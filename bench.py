@@ -32,8 +32,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c3_step", choices=["c2_layer", "c3_step", "c4_skew", "c5_stream", "c6_paper"],
-                    help="c5_stream / c6_paper: streaming rollouts, a step = one chunk (4 attention passes over all layers, "
+    ap.add_argument("--workload", default="c3_step", choices=["c2_layer", "c3_step", "c4_skew", "c5_stream", "c6_paper", "c7_headwin"],
+                    help="c5_stream / c6_paper / c7_headwin: streaming rollouts, a step = one chunk (4 attention passes over all layers, "
                          "then append + index build per layer); --steps = chunks from an empty cache (default there: "
                          "the whole rollout)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
@@ -59,7 +59,7 @@ def main():
     B.lib()                                           # fail loudly if libpf.so is missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    if args.workload in ("c5_stream", "c6_paper"):
+    if args.workload in ("c5_stream", "c6_paper", "c7_headwin"):
         return stream_bench(args, B, synth, dev)
     w = synth.WORKLOADS[args.workload]
     n_layers = args.layers or w.n_layers

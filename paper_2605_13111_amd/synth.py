@@ -31,6 +31,9 @@ WORKLOADS = {
     # the paper's own policy set (sink 3, recent 4, capacities 4/4/2, strided Anchor, capped Wave) rolled out in
     # 3-frame chunks to a 240-frame history: mild raggedness, short key lists
     "c6_paper": Workload("c6_paper", 30, 12, 128, 1560, 3, 240),
+    # the "Head Classification only" variant of the component ablation: every head keeps the sink frames and a
+    # neighbouring window whose length depends on its type (12 / 10 / 5 frames for Anchor / Wave / Veil)
+    "c7_headwin": Workload("c7_headwin", 30, 12, 128, 1560, 3, 240),
 }
 
 
@@ -99,6 +102,8 @@ def policies(workload, layer=0, extra_frames=0):
         return drawn_policies(w.n_heads, 7000 + layer, cap_frames)
     if w.name == "c6_paper":
         return paper_default_policies(w.n_heads, 8000 + layer, cap_frames)
+    if w.name == "c7_headwin":
+        return head_window_policies(w.n_heads, 8000 + layer)
     raise KeyError(w.name)
 
 
@@ -115,6 +120,20 @@ def paper_default_policies(n_heads, seed, max_frames, wave_period=6):
             pols.append(wave(wave_period, min(max_frames, 3 + 4 + 5 * wave_period), cap=4, sink=3, recent=4))
         else:
             pols.append(veil_merged(3, 4, 2, 2))
+    return pols
+
+
+def head_window_policies(n_heads, seed, windows=(12, 10, 5), sink=3):
+    """Type-specific neighbouring windows (component ablation, "Head Classification" variant): a head of type
+    Anchor / Wave / Veil keeps the sink frames plus its last 12 / 10 / 5 frames; types drawn 40/30/30 as in
+    ``paper_default_policies``.  A sink + recent-window policy is what the library calls a Veil head without
+    merging, whatever the head's type."""
+    g = _cpu_gen(seed)
+    u = torch.rand(n_heads, generator=g)
+    pols = []
+    for h in range(n_heads):
+        win = windows[0] if u[h] < 0.4 else windows[1] if u[h] < 0.7 else windows[2]
+        pols.append(veil(sink, win))
     return pols
 
 

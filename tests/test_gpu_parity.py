@@ -190,6 +190,16 @@ def test_paper_default_policies_at_model_shape(variant):
     print("paper-default policies: max-abs %.2e rel %.2e" % (a, r))
 
 
+def test_head_window_ablation_policies_at_model_shape():
+    """The component ablation's "Head Classification" variant: sink 3 plus a neighbouring window of 12 / 10 / 5
+    frames by head type, after 8 three-frame chunks at model shape (windows full, evictions under way)."""
+    pols = synth.head_window_policies(12, 8002)
+    assert sorted({p.recent for p in pols}) == [5, 10, 12]
+    rows = G.sample_rows(4680, 32, 37, extra=(1559, 1560))
+    a, r = G.run_case(pols, 1560, 128, [3] * 8, 4680, seed=37, rows=rows, check_every_append=False, label="head-windows")
+    print("head-window policies: max-abs %.2e rel %.2e" % (a, r))
+
+
 def test_veil_cache_merging(variant):
     """Veil heads with cache merging (Sec. 4.2) next to the other head types: merged frames bit-exact in the pool
     after every append (windows of 2 and of 3 frames, token counts that 3 does and does not divide), merged
