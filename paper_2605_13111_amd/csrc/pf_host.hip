@@ -56,11 +56,13 @@ int pf_resolve_seg_tiles(int seg_tiles) {
 // blocks per compute unit the finish time depends strongly on how the block count per die divides by its 32
 // compute units, so the segment length is chosen by replaying that schedule on the host for a few
 // candidate lengths (costs: one key tile = 1, fixed cost per block, extra cost when a partial result has
-// to be parked and merged) and keeping the shortest finish.
+// to be parked, and for a head's last segment the cost of reading back every partial it merges) and keeping
+// the shortest finish.
 static const int kSegCandidates[] = {48, 56, 64, 72, 80, 96, 112, 128, 144, 160, 176, 192, 224, 256, 320, 384};
 constexpr int PF_AUTO_MIN_SEG = 48;                 // smallest candidate: bounds the partial-result workspace
 constexpr double PF_BLOCK_COST = 8.0;               // set-up + first fetch + store, in key-tile times (fitted to timings)
-constexpr double PF_SPLIT_COST = 2.0;               // parking / merging a partial result
+constexpr double PF_SPLIT_COST = 2.0;               // parking a partial result
+constexpr double PF_MERGE_COST = 2.0;               // per partial read back by the merging block (fitted to timings)
 
 static double model_finish(const std::vector<int> &n_kvt, const std::vector<int> &order, int n_qt, int seg_tiles,
                            int slots_per_die) {
@@ -76,8 +78,9 @@ static double model_finish(const std::vector<int> &n_kvt, const std::vector<int>
     for (int sgi = 0; sgi < nseg; ++sgi, ++k) {
       const int row = k / PF_NUM_XCD, col = k % PF_NUM_XCD;
       const int xcd = (row & 1) ? PF_NUM_XCD - 1 - col : col;
+      // the merge falls to whichever segment arrives last; the replay charges it to the last one launched
       const double cost = pf_seg_begin(nk, nseg, sgi + 1) - pf_seg_begin(nk, nseg, sgi) + PF_BLOCK_COST +
-                          (nseg > 1 ? PF_SPLIT_COST : 0.0);
+                          (nseg > 1 ? PF_SPLIT_COST : 0.0) + (nseg > 1 && sgi == nseg - 1 ? PF_MERGE_COST * nseg : 0.0);
       for (int q = 0; q < n_qt; ++q) {
         const double t = die[xcd].top() + cost;
         die[xcd].pop();
