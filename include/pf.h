@@ -142,7 +142,7 @@ typedef struct pf_index {
   int32_t n_blocks;               /* workgroups of the attention launch */
   int32_t n_partials;             /* partial-result slots the launch uses */
   int32_t variant;                /* kernel variant the plan was built for */
-  int32_t reserved;               /* segment length the library chose (0 when the caller fixed it); start at 0 */
+  int32_t reserved;               /* longest segment length the library planned (0 when the caller fixed it); start at 0 */
 } pf_index;
 
 /*

@@ -15,6 +15,8 @@
 //                     the V rows instead, since a sum over keys has no order)
 // so every lane owns ONE query column: the running maximum and sum of the online softmax live in
 // one register each and need a single exchange with lane^32 per tile.
+#include <stddef.h>
+#include <stdlib.h>
 #include "pf_internal.h"
 #include <utility>
 
@@ -41,13 +43,19 @@ struct AttnParams {
   const int32_t *sel_count, *sel_slots;
   const PfWorkItem *items;
   int32_t *counters;
+  int32_t *tickets;     // work-queue mode: next entry of each die's queue [PF_NUM_XCD], then the count of workgroups done; null = one item per workgroup
   float *workspace;
-  int max_sel, tpf, q_tokens, n_qt;
+  int max_sel, tpf, q_tokens, n_qt, queue_len;
   float scale_log2;     // softmax scale * log2(e)
   // chunk tensors (q, k_cur, v_cur, out): element strides between tokens of a head and between heads
   // (packed [heads][tokens][D]: D and q_tokens*D; the model's [tokens][heads][D]: heads*D and D)
   long long tok_stride, head_stride;
 };
+
+template <class T>
+__device__ __forceinline__ T *as_global(T *p) {
+  return (T *)(__attribute__((address_space(1))) T *)(unsigned long long)p;
+}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -339,12 +347,12 @@ __device__ __forceinline__ void st_dev4(float *p, f32x4 v) {
 
 template <int D, int NQB, int NWAVES = ATT_WAVES>
 __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkItem &it, f32x16 (&o)[NQB][D / 32],
-                                              float (&m_run)[NQB], float (&l_run)[NQB], float *sStage, int32_t *sFlagp) {
+                                              float (&m_run)[NQB], float (&l_run)[NQB], float *sStage, int32_t *sFlagp,
+                                              int tid) {
   constexpr int BQ = NWAVES * 32 * NQB;
   constexpr int NT = NWAVES * 64;
   constexpr int NDB = D / 32;
   constexpr int LD = D + 4;                        // row stride of the staged tile: 16-byte writes of 16 rows hit all banks
-  const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int h = it.head;
@@ -472,9 +480,8 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
 // Common set-up of a workgroup: its work item, the head's key layout, its Q^T fragments.
 // ---------------------------------------------------------------------------------------------------
 template <int D>
-__device__ __forceinline__ void attn_setup_head(const AttnParams &P, const PfWorkItem &it, HeadKV &H) {
+__device__ __forceinline__ void attn_setup_head(const AttnParams &P, const PfWorkItem &it, HeadKV &H, int tid) {
   constexpr int CPR = D / 8;
-  const int tid = threadIdx.x;
   const int h = it.head;
   H.n_sel = P.sel_count[h];
   H.tpf = P.tpf;
@@ -492,8 +499,8 @@ __device__ __forceinline__ void attn_setup_head(const AttnParams &P, const PfWor
 }
 // Q^T fragments: lane (l32, g) holds, for its query row, d = 16*ks + 8*g .. +7
 template <int D, int NQB>
-__device__ __forceinline__ void attn_load_q(const AttnParams &P, const PfWorkItem &it, bf16x8 (&qf)[NQB][D / 16]) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+__device__ __forceinline__ void attn_load_q(const AttnParams &P, const PfWorkItem &it, bf16x8 (&qf)[NQB][D / 16], int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const __bf16 *qh = P.q + (size_t)it.head * P.head_stride;
 #pragma unroll
@@ -505,8 +512,8 @@ __device__ __forceinline__ void attn_load_q(const AttnParams &P, const PfWorkIte
 }
 template <int D, int NQB>
 __device__ __forceinline__ void attn_setup(const AttnParams &P, const PfWorkItem &it, HeadKV &H, bf16x8 (&qf)[NQB][D / 16]) {
-  attn_setup_head<D>(P, it, H);
-  attn_load_q<D, NQB>(P, it, qf);
+  attn_setup_head<D>(P, it, H, threadIdx.x);
+  attn_load_q<D, NQB>(P, it, qf, threadIdx.x);
 }
 
 template <int D, int NQB>
@@ -537,7 +544,7 @@ __device__ __forceinline__ void attn_item_classic(const AttnParams &P, const PfW
   float m_run[NQB], l_run[NQB];
   attn_zero<D, NQB>(o, m_run, l_run);
   classic_loop<D, NQB>(H, it.kt0, it.kt1, qf, o, m_run, l_run, sK, sV, P.scale_log2);
-  attn_epilogue<D, NQB>(P, it, o, m_run, l_run, (float *)&sK[0][0], sFlag);
+  attn_epilogue<D, NQB>(P, it, o, m_run, l_run, (float *)&sK[0][0], sFlag, threadIdx.x);
 }
 
 template <int D>
@@ -654,7 +661,7 @@ __device__ __forceinline__ void pp_wait_frag(u32x2 (&vl)[16], u32x2 (&vh)[16], u
 }
 
 template <int D>
-__global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams P) {
+__global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams) {
   static_assert(D == 128, "tile layouts are written for 256-byte rows");
   constexpr int BK = PF_BK;
   constexpr int NKS = D / 16, NDB = D / 32;
@@ -665,18 +672,74 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   static_assert((PP_KSTAGES + PP_VSTAGES) * PP_TILE_BYTES >= attn_stage_floats(PP_WAVES * 32, D) * 4, "output staging fits");
   __shared__ __attribute__((aligned(1024))) char smem[(PP_KSTAGES + PP_VSTAGES) * PP_TILE_BYTES];
   __shared__ int32_t sFlag;
+  __shared__ int32_t sNext;
   char (*sK)[PP_TILE_BYTES] = (char (*)[PP_TILE_BYTES])smem;
   char (*sV)[PP_TILE_BYTES] = sK + PP_KSTAGES;
+  const int tid0 = threadIdx.x;
 
-  const PfWorkItem it = P.items[blockIdx.x];
-  if (it.head < 0) return;
-  const int tid = threadIdx.x;
+  // ---- work queue.  The items of die x are entries x, x + 8, x + 16, ... of the list, in the order the plan
+  // wants them started.  One workgroup per compute unit is launched; workgroup b runs on die b % 8 and takes
+  // the next entry of that die's queue (so the query tiles of one key segment still run side by side on one
+  // die and share its L2), and when that queue is empty it takes from the next die's, and so on: the dies do
+  // not run at the same speed, and without this the launch ends when the slowest die does.  Every workgroup
+  // leaves the loop after finding all eight queues empty; tickets only grow, so that always happens.  The last
+  // workgroup to leave puts the tickets back to zero for the next launch. ----
+  // The parameters are read again from the kernel-argument segment for every item (a few scalar loads): held in
+  // registers across the loop they would crowd out the item's own state.
+  typedef const __attribute__((address_space(4))) unsigned long long *karg_t;
+  static_assert(sizeof(AttnParams) % 8 == 0, "parameters are copied as 8-byte words");
+  struct ParamWords { unsigned long long w[sizeof(AttnParams) / 8]; };
+  auto load_params = [&]() {
+    int opaque_zero = 0;                       // hides from the compiler that every call reads the same words
+    asm volatile("" : "+s"(opaque_zero));
+    karg_t karg = (karg_t)__builtin_amdgcn_kernarg_segment_ptr() + __builtin_amdgcn_readfirstlane(opaque_zero);
+    ParamWords pw;
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(AttnParams) / 8); ++i) pw.w[i] = karg[i];
+    AttnParams R = __builtin_bit_cast(AttnParams, pw);
+    // pointers rebuilt from raw words: say again that they point to global memory
+    R.q = as_global(R.q), R.k_cur = as_global(R.k_cur), R.v_cur = as_global(R.v_cur), R.k_pool = as_global(R.k_pool);
+    R.v_pool = as_global(R.v_pool), R.out = as_global(R.out), R.sel_count = as_global(R.sel_count);
+    R.sel_slots = as_global(R.sel_slots), R.items = as_global(R.items), R.counters = as_global(R.counters);
+    R.tickets = as_global(R.tickets), R.workspace = as_global(R.workspace);
+    return R;
+  };
+  int hop_v = 0;                               // dies given up so far; kept in a vector register between items
+  while (true) {
+  asm volatile("" : "+v"(hop_v));
+  int hop = __builtin_amdgcn_readfirstlane(hop_v);
+  const AttnParams P = load_params();
+  int item_idx = -1;
+  if (P.tickets == nullptr) {
+    if (hop == 0) item_idx = blockIdx.x;
+    hop = PF_NUM_XCD;
+  } else {
+    const int home = blockIdx.x % PF_NUM_XCD;
+    while (hop < PF_NUM_XCD) {
+      const int x = (home + hop) % PF_NUM_XCD;
+      if (tid0 == 0) sNext = atomicAdd(&P.tickets[x], 1);
+      __syncthreads();
+      const int j = __builtin_amdgcn_readfirstlane(sNext);
+      __syncthreads();
+      if (j < P.queue_len) {
+        item_idx = j * PF_NUM_XCD + x;
+        break;
+      }
+      ++hop;
+    }
+  }
+  hop_v = hop;
+  if (item_idx < 0) break;
+  const PfWorkItem it = P.items[item_idx];
+  if (it.head < 0) continue;
+  int tid = tid0;
+  asm volatile("" : "+v"(tid));               // per-lane constants are worked out anew for each item, not kept across the loop
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = wave >> 2;
   const int l32 = lane & 31, g = lane >> 5;
   HeadKV H;
-  attn_setup_head<D>(P, it, H);
+  attn_setup_head<D>(P, it, H, tid);
   f32x16 o[1][NDB];
   float m_run[1], l_run[1];
   attn_zero<D, 1>(o, m_run, l_run);
@@ -772,7 +835,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     copy_tile_now(it.kt0 + 2, pos, 2, 2);
   }
   bf16x8 qf[1][NKS];
-  attn_load_q<D, 1>(P, it, qf);
+  attn_load_q<D, 1>(P, it, qf, tid);
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[0][ks]));
   __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -947,12 +1010,35 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   m_phase(TagT(), TagF(), 0, sv, 0);
   if (grp == 0) __builtin_amdgcn_s_barrier();                  // group 0 waits for group 1's last phase
   __syncthreads();
-  attn_epilogue<D, 1, PP_WAVES>(P, it, o, m_run, l_run, (float *)&sK[0][0], &sFlag);
+  const AttnParams Pe = load_params();                         // read again: nothing of it is held through the loop above
+  attn_epilogue<D, 1, PP_WAVES>(Pe, it, o, m_run, l_run, (float *)&sK[0][0], &sFlag, tid);
+  }
+  int32_t *tickets = load_params().tickets;
+  if (tickets != nullptr && tid0 == 0) {
+    const int done = atomicAdd(&tickets[PF_NUM_XCD], 1);
+    if (done == (int)gridDim.x - 1) {
+      for (int x = 0; x <= PF_NUM_XCD; ++x) atomicExch(&tickets[x], 0);
+    }
+  }
+}
+
+// Workgroups of the pipelined kernel that are resident at once: its LDS rings leave room for one per compute unit.
+static int pp_resident_workgroups() {
+  static int n_cu[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (n_cu[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    n_cu[dev] = n;
+  }
+  return n_cu[dev];
 }
 
 static int launch_attn(const AttnParams &P, int head_dim, int variant, int n_blocks, hipStream_t stream) {
   if (head_dim == 128 && variant == 1)
-    hipLaunchKernelGGL((pf_attn_pp_kernel<128>), dim3(n_blocks), dim3(PP_WAVES * 64), 0, stream, P);
+    hipLaunchKernelGGL((pf_attn_pp_kernel<128>), dim3(P.tickets ? pf_min(n_blocks, pp_resident_workgroups()) : n_blocks),
+                       dim3(PP_WAVES * 64), 0, stream, P);
   else if (head_dim == 128 && variant == 0)
     hipLaunchKernelGGL((pf_attn_kernel<128>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
   else if (head_dim == 64 && variant == 0)
@@ -1003,6 +1089,9 @@ static int attn_fwd_impl(const pf_pool *pool, const pf_index *index, const void 
   P.sel_slots = index->sel_slots;
   P.items = (const PfWorkItem *)(w + L.items_off);
   P.counters = (int32_t *)(w + L.counters_off);
+  const bool queue = pf_attn_queue_mode(index->variant);
+  P.tickets = queue ? P.counters + (size_t)pool->n_heads * n_qt : nullptr;
+  P.queue_len = index->n_blocks / PF_NUM_XCD;
   P.workspace = (float *)workspace;
   P.max_sel = index->max_sel;
   P.tpf = pool->tokens_per_frame;

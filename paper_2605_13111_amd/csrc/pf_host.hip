@@ -3,6 +3,7 @@
 #include <string.h>
 #include <algorithm>
 #include <functional>
+#include <mutex>
 #include <queue>
 #include <vector>
 #include "pf_internal.h"
@@ -50,76 +51,202 @@ int pf_resolve_seg_tiles(int seg_tiles) {
   return seg_tiles < PF_MIN_SEG_TILES ? PF_MIN_SEG_TILES : seg_tiles;
 }
 
-// ---- automatic segment length --------------------------------------------------------------------
-// The launch is a list of equal-priority blocks, one per (head, key segment, query tile).  Block i goes to
-// die i % 8; a die starts its next block on the first compute unit that frees up.  With three or four
-// blocks per compute unit the finish time depends strongly on how the block count per die divides by its 32
-// compute units, so the segment length is chosen by replaying that schedule on the host for a few
-// candidate lengths (costs: one key tile = 1, fixed cost per block, extra cost when a partial result has
-// to be parked, and for a head's last segment the cost of reading back every partial it merges) and keeping
-// the shortest finish.
+// ---- automatic segment lengths ------------------------------------------------------------------
+// The launch is a list of blocks, one per (head, key segment, query tile); block i belongs to die i % 8.
+//   * one block per workgroup (kernel 0): the hardware sends block i to die i % 8, and a die starts its next
+//     block on the first compute unit that frees up;
+//   * work queue (kernel 1): one resident workgroup per compute unit takes the next block of its die's list, and
+//     from the next die's list once its own is empty.
+// With three or four blocks per compute unit the finish time depends strongly on how the blocks pack, so the
+// plan is chosen by replaying the schedule on the host (costs: one key tile = 1, a fixed cost per block, an
+// extra cost when a partial result has to be parked, and for a head's last segment the cost of reading back
+// every partial it merges; the constants are fitted to per-layer timings of every candidate) and keeping
+// the shortest finish:
+//   1. one segment length for every head, from a list of candidates;
+//   2. starting from that, heads with the same key count try every segment count of their own while the
+//      others stay fixed, a few rounds (pools of up to PF_PLAN_HEADS heads).
+// Plans are remembered per (key tiles of every head, query tiles, kernel, mode), so a steady-state step pays a
+// table lookup.
 static const int kSegCandidates[] = {48, 56, 64, 72, 80, 96, 112, 128, 144, 160, 176, 192, 224, 256, 320, 384};
-constexpr int PF_AUTO_MIN_SEG = 48;                 // smallest candidate: bounds the partial-result workspace
-constexpr double PF_BLOCK_COST = 8.0;               // set-up + first fetch + store, in key-tile times (fitted to timings)
-constexpr double PF_SPLIT_COST = 2.0;               // parking a partial result
-constexpr double PF_MERGE_COST = 2.0;               // per partial read back by the merging block (fitted to timings)
+constexpr int PF_AUTO_MIN_SEG = 48;                 // shortest planned segment: bounds the partial-result workspace
+struct PlanCosts {
+  double block, split, merge;                       // per block; per parked partial; per partial read back by the merging block
+};
+static const PlanCosts kCostsDirect = {8.0, 2.0, 2.0};
+static const PlanCosts kCostsQueue = {4.0, 2.0, 3.0};
+constexpr int PF_PLAN_ROUNDS = 3;
+constexpr int PF_PLAN_MAX_NSEG = 16;                // segment counts tried per head in step 2
+constexpr double PF_PLAN_MIN_GAIN = 0.01;           // step 2 must beat step 1 by this much to be used
+constexpr size_t PF_PLAN_CACHE = 256;
 
-static double model_finish(const std::vector<int> &n_kvt, const std::vector<int> &order, int n_qt, int seg_tiles,
-                           int slots_per_die) {
+// Finish time of the launch in which head h has key tiles n_kvt[h] cut into segments of at most seg[h] tiles.
+static double model_finish(const std::vector<int> &n_kvt, const std::vector<int> &seg, int n_qt, int slots_per_die,
+                           bool queue) {
   typedef std::priority_queue<double, std::vector<double>, std::greater<double> > MinHeap;
-  std::vector<MinHeap> die(PF_NUM_XCD);
-  for (int x = 0; x < PF_NUM_XCD; ++x)
-    for (int c = 0; c < slots_per_die; ++c) die[x].push(0.0);
-  double finish = 0.0;
+  const PlanCosts &C = queue ? kCostsQueue : kCostsDirect;
+  const int H = (int)n_kvt.size();
+  // heads by descending segment length (ties: head id), as the index kernel ranks them
+  std::vector<int> order(H), nsegs(H), len(H);
+  for (int h = 0; h < H; ++h) {
+    order[h] = h;
+    nsegs[h] = pf_max(1, pf_ceil_div(n_kvt[h], seg[h]));
+    len[h] = pf_ceil_div(n_kvt[h], nsegs[h]);
+  }
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return len[a] > len[b]; });
+  // per die: the cost of each team (n_qt equal blocks), in launch order
+  std::vector<std::vector<double> > teams(PF_NUM_XCD);
   int k = 0;                                         // team rank, as in the index kernel
-  for (size_t o = 0; o < order.size(); ++o) {
-    const int nk = n_kvt[order[o]];
-    const int nseg = pf_max(1, pf_ceil_div(nk, seg_tiles));
+  for (int o = 0; o < H; ++o) {
+    const int nk = n_kvt[order[o]], nseg = nsegs[order[o]];
     for (int sgi = 0; sgi < nseg; ++sgi, ++k) {
       const int row = k / PF_NUM_XCD, col = k % PF_NUM_XCD;
       const int xcd = (row & 1) ? PF_NUM_XCD - 1 - col : col;
       // the merge falls to whichever segment arrives last; the replay charges it to the last one launched
-      const double cost = pf_seg_begin(nk, nseg, sgi + 1) - pf_seg_begin(nk, nseg, sgi) + PF_BLOCK_COST +
-                          (nseg > 1 ? PF_SPLIT_COST : 0.0) + (nseg > 1 && sgi == nseg - 1 ? PF_MERGE_COST * nseg : 0.0);
-      for (int q = 0; q < n_qt; ++q) {
-        const double t = die[xcd].top() + cost;
-        die[xcd].pop();
-        die[xcd].push(t);
-        finish = t > finish ? t : finish;
+      teams[xcd].push_back(pf_seg_begin(nk, nseg, sgi + 1) - pf_seg_begin(nk, nseg, sgi) + C.block +
+                           (nseg > 1 ? C.split : 0.0) + (nseg > 1 && sgi == nseg - 1 ? C.merge * nseg : 0.0));
+    }
+  }
+  double finish = 0.0;
+  if (!queue) {
+    for (int x = 0; x < PF_NUM_XCD; ++x) {
+      MinHeap cu;
+      for (int c = 0; c < slots_per_die; ++c) cu.push(0.0);
+      for (size_t t = 0; t < teams[x].size(); ++t)
+        for (int q = 0; q < n_qt; ++q) {
+          const double e = cu.top() + teams[x][t];
+          cu.pop();
+          cu.push(e);
+          finish = e > finish ? e : finish;
+        }
+    }
+    return finish;
+  }
+  // work queue: the worker that frees up first takes the next block of its die's list, else of the next die's
+  typedef std::pair<double, int> Worker;             // (time it is free, home die)
+  std::priority_queue<Worker, std::vector<Worker>, std::greater<Worker> > workers;
+  for (int w = 0; w < PF_NUM_XCD * slots_per_die; ++w) workers.push(Worker(0.0, w % PF_NUM_XCD));
+  size_t next[PF_NUM_XCD] = {};
+  while (!workers.empty()) {
+    const Worker w = workers.top();
+    workers.pop();
+    for (int hop = 0; hop < PF_NUM_XCD; ++hop) {
+      const int x = (w.second + hop) % PF_NUM_XCD;
+      if (next[x] < teams[x].size() * (size_t)n_qt) {
+        const double e = w.first + teams[x][next[x] / n_qt];
+        ++next[x];
+        finish = e > finish ? e : finish;
+        workers.push(Worker(e, w.second));
+        break;
       }
     }
   }
   return finish;
 }
 
-int pf_auto_seg_tiles(const pf_pool *pool, int T, int q_tokens, int variant) {
+namespace {
+struct PlanEntry {
+  std::vector<int> key;                              // n_kvt of every head, then n_qt, kernel and mode
+  PfSegPlan plan;
+};
+std::mutex g_plan_mutex;
+std::vector<PlanEntry> g_plan_cache;
+size_t g_plan_next = 0;
+}  // namespace
+
+void pf_auto_plan(const pf_pool *pool, int T, int q_tokens, int variant, bool queue, PfSegPlan *plan) {
+  const int H = pool->n_heads;
   const int n_qt = pf_ceil_div(q_tokens, pf_variant_bq(variant));
   const int slots_per_die = 32 * (variant == 0 ? 2 : 1);          // workgroups resident per die
-  std::vector<int> n_kvt(pool->n_heads);
+  memset(plan, 0, sizeof(*plan));
+  plan->uniform = PF_DEFAULT_SEG_TILES;
+  std::vector<int> n_kvt(H);
   long long total = 0;
-  for (int h = 0; h < pool->n_heads; ++h) {
+  for (int h = 0; h < H; ++h) {
     const int nsel = pf_sel_count_impl(pool->policy_host[h], T);
     n_kvt[h] = pf_ceil_div(nsel * pool->tokens_per_frame + q_tokens, PF_BK);
     total += pf_ceil_div(n_kvt[h], PF_AUTO_MIN_SEG);
   }
-  if (total * n_qt > 50000) return PF_DEFAULT_SEG_TILES;          // keep the replay cheap on huge launches
-  int best = PF_DEFAULT_SEG_TILES;
+  if (total * n_qt > 50000) return;                               // keep the replay cheap on huge launches
+
+  std::vector<int> key(n_kvt);
+  key.push_back(n_qt);
+  key.push_back(variant * 2 + (queue ? 1 : 0));
+  {
+    std::lock_guard<std::mutex> lock(g_plan_mutex);
+    for (size_t i = 0; i < g_plan_cache.size(); ++i)
+      if (g_plan_cache[i].key == key) {
+        *plan = g_plan_cache[i].plan;
+        return;
+      }
+  }
+
+  // step 1: one length for all
+  std::vector<int> seg(H);
   double best_t = 0.0;
-  std::vector<int> order(pool->n_heads);
   for (size_t ci = 0; ci < sizeof(kSegCandidates) / sizeof(kSegCandidates[0]); ++ci) {
-    const int seg = kSegCandidates[ci];
-    // heads by descending segment length (ties: head id), as the index kernel ranks them
-    for (int h = 0; h < pool->n_heads; ++h) order[h] = h;
-    std::vector<int> len(pool->n_heads);
-    for (int h = 0; h < pool->n_heads; ++h) len[h] = pf_ceil_div(n_kvt[h], pf_max(1, pf_ceil_div(n_kvt[h], seg)));
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return len[a] > len[b]; });
-    const double t = model_finish(n_kvt, order, n_qt, seg, slots_per_die);
+    std::fill(seg.begin(), seg.end(), kSegCandidates[ci]);
+    const double t = model_finish(n_kvt, seg, n_qt, slots_per_die, queue);
     if (best_t == 0.0 || t < best_t * 0.995) {       // a longer segment must win clearly: it costs fewer partials
       best_t = best_t == 0.0 ? t : (t < best_t ? t : best_t);
-      best = seg;
+      plan->uniform = kSegCandidates[ci];
     }
   }
-  return best;
+  std::fill(seg.begin(), seg.end(), plan->uniform);
+  const double uniform_t = model_finish(n_kvt, seg, n_qt, slots_per_die, queue);
+
+  // step 2: per key count, the segment count of its own
+  if (H <= PF_PLAN_HEADS && !getenv("PF_PLAN_UNIFORM")) {
+    std::vector<int> distinct(n_kvt);
+    std::sort(distinct.begin(), distinct.end());
+    distinct.erase(std::unique(distinct.begin(), distinct.end()), distinct.end());
+    double cur_t = uniform_t;
+    for (int round = 0; round < PF_PLAN_ROUNDS; ++round) {
+      bool changed = false;
+      for (size_t d = 0; d < distinct.size(); ++d) {
+        const int nk = distinct[d];
+        int cur_seg = 0;
+        for (int h = 0; h < H; ++h)
+          if (n_kvt[h] == nk) cur_seg = seg[h];
+        int best_seg = cur_seg;
+        for (int n = 1; n <= PF_PLAN_MAX_NSEG; ++n) {
+          const int cand = pf_ceil_div(nk, n);
+          if (cand < PF_AUTO_MIN_SEG && n > 1) break;
+          if (cand == cur_seg) continue;
+          for (int h = 0; h < H; ++h)
+            if (n_kvt[h] == nk) seg[h] = pf_max(cand, PF_AUTO_MIN_SEG);
+          const double t = model_finish(n_kvt, seg, n_qt, slots_per_die, queue);
+          if (t < cur_t * 0.998) {
+            cur_t = t;
+            best_seg = pf_max(cand, PF_AUTO_MIN_SEG);
+          }
+        }
+        for (int h = 0; h < H; ++h)
+          if (n_kvt[h] == nk) seg[h] = best_seg;
+        changed = changed || best_seg != cur_seg;
+      }
+      if (!changed) break;
+    }
+    if (cur_t < uniform_t * (1.0 - PF_PLAN_MIN_GAIN)) {
+      plan->per_head = 1;
+      for (int h = 0; h < H; ++h) plan->seg[h] = (uint16_t)pf_min(seg[h], 65535);
+    }
+  }
+
+  std::lock_guard<std::mutex> lock(g_plan_mutex);
+  PlanEntry e;
+  e.key = key;
+  e.plan = *plan;
+  if (g_plan_cache.size() < PF_PLAN_CACHE) {
+    g_plan_cache.push_back(e);
+  } else {
+    g_plan_cache[g_plan_next] = e;
+    g_plan_next = (g_plan_next + 1) % PF_PLAN_CACHE;
+  }
+}
+
+bool pf_attn_queue_mode(int variant) {
+  const char *e = getenv("PF_ATTN_QUEUE");
+  return variant == 1 && !(e && atoi(e) == 0);
 }
 
 int pf_resolve_variant(int head_dim) {
@@ -129,7 +256,7 @@ int pf_resolve_variant(int head_dim) {
   return head_dim == 128 ? v : 0;                   // kernel 1 exists for head_dim 128 only
 }
 
-void pf_host_plan(const pf_pool *pool, int T, int q_tokens, int variant, int seg_tiles,
+void pf_host_plan(const pf_pool *pool, int T, int q_tokens, int variant, const PfSegPlan &plan,
                   int *n_teams, int *n_blocks, int *n_partials, int *max_sel_needed) {
   const int n_qt = pf_ceil_div(q_tokens, pf_variant_bq(variant));
   long long teams = 0, parts = 0;
@@ -137,7 +264,7 @@ void pf_host_plan(const pf_pool *pool, int T, int q_tokens, int variant, int seg
   for (int h = 0; h < pool->n_heads; ++h) {
     const int nsel = pf_sel_count_impl(pool->policy_host[h], T);
     max_sel = pf_max(max_sel, nsel);
-    const PfHeadPlan hp = pf_plan_head(nsel * pool->tokens_per_frame + q_tokens, seg_tiles);
+    const PfHeadPlan hp = pf_plan_head(nsel * pool->tokens_per_frame + q_tokens, plan.of(h));
     teams += hp.nseg;
     if (hp.nseg > 1) parts += (long long)hp.nseg * n_qt;
   }

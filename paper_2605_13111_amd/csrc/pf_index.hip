@@ -1,6 +1,7 @@
 // Frame-index build: per-head frame selection (Sec. 4.2), boundary indices of the flattened ragged
 // history (Sec. 4.3) and the launch plan of the attention kernel.  One small launch per layer.
 #include <stdlib.h>
+#include <string.h>
 #include "pf_internal.h"
 
 constexpr int INDEX_THREADS = 256;
@@ -15,8 +16,9 @@ struct IndexParams {
   int32_t *counters, *scratch;
   PfWorkItem *items;
   long long total_slots;
-  int n_heads, T, tpf, max_sel, q_tokens, n_qt, bq, seg_tiles, variant;
+  int n_heads, T, tpf, max_sel, q_tokens, n_qt, bq, variant;
   int host_teams, host_blocks, host_partials;
+  PfSegPlan plan;
 };
 
 // Does head `p` attend to resident frame f (history length T)?  `rank` = number of resident
@@ -131,12 +133,12 @@ __global__ __launch_bounds__(INDEX_THREADS) void pf_build_index_kernel(IndexPara
       // The host sized the launch from the closed-form count; a mismatch means the pool does not hold
       // what the policy asks for (it was not filled through pf_cache_append).
       if (n != pf_sel_count_impl(pol, P.T) || n > P.max_sel) atomicExch(&s_error, 1);
-      const PfHeadPlan hp = pf_plan_head(n * P.tpf + P.q_tokens, P.seg_tiles);
+      const PfHeadPlan hp = pf_plan_head(n * P.tpf + P.q_tokens, P.plan.of(h));
       s_nseg[h] = hp.nseg;
       s_nkvt[h] = hp.n_kvt;
     }
   }
-  for (int i = tid; i < P.n_heads * P.n_qt; i += INDEX_THREADS) P.counters[i] = 0;
+  for (int i = tid; i < P.n_heads * P.n_qt + PF_QUEUE_INTS; i += INDEX_THREADS) P.counters[i] = 0;
   __syncthreads();
 
   // ---- boundaries (exclusive prefix sum, batch-head order) and per-head plan offsets ----
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(INDEX_THREADS) void pf_build_index_kernel(IndexPara
     P.header->n_teams = n_teams;
     P.header->n_qt = P.n_qt;
     P.header->variant = P.variant;
-    P.header->seg_tiles = P.seg_tiles;
+    P.header->seg_tiles = P.plan.per_head ? 0 : P.plan.uniform;
     P.header->q_tokens = P.q_tokens;
   }
   for (int b = tid; b < P.host_blocks; b += INDEX_THREADS) P.items[b].head = -1;
@@ -215,19 +217,17 @@ extern "C" int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens
   if (index->seg_tiles < 0) return PF_ERR_INVALID_ARG;
 
   const int variant = pf_resolve_variant(pool->head_dim);
-  // segment length: the caller's, else the PF_SEG_TILES override, else chosen for this launch (and kept while
-  // the history length, the query count and the kernel stay the same)
-  int seg_tiles;
-  if (index->seg_tiles > 0 || getenv("PF_SEG_TILES")) {
-    seg_tiles = pf_resolve_seg_tiles(index->seg_tiles);
-  } else if (index->reserved >= PF_MIN_SEG_TILES && index->T_built == pool->T_host && index->q_tokens == q_tokens &&
-             index->variant == variant) {
-    seg_tiles = index->reserved;
+  // segment lengths: the caller's, else the PF_SEG_TILES override, else planned for this launch
+  const bool fixed = index->seg_tiles > 0 || getenv("PF_SEG_TILES");
+  PfSegPlan plan;
+  if (fixed) {
+    memset(&plan, 0, sizeof(plan));
+    plan.uniform = pf_resolve_seg_tiles(index->seg_tiles);
   } else {
-    seg_tiles = pf_auto_seg_tiles(pool, pool->T_host, q_tokens, variant);
+    pf_auto_plan(pool, pool->T_host, q_tokens, variant, pf_attn_queue_mode(variant), &plan);
   }
   int n_teams, n_blocks, n_partials, max_sel_needed;
-  pf_host_plan(pool, pool->T_host, q_tokens, variant, seg_tiles, &n_teams, &n_blocks, &n_partials, &max_sel_needed);
+  pf_host_plan(pool, pool->T_host, q_tokens, variant, plan, &n_teams, &n_blocks, &n_partials, &max_sel_needed);
   if (max_sel_needed > index->max_sel) return PF_ERR_CAPACITY;
   const int n_qt = pf_ceil_div(q_tokens, pf_variant_bq(variant));
   const PfWorkLayout L = pf_work_layout(pool->n_heads, n_qt, n_blocks);
@@ -256,7 +256,7 @@ extern "C" int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens
   P.q_tokens = q_tokens;
   P.n_qt = n_qt;
   P.bq = pf_variant_bq(variant);
-  P.seg_tiles = seg_tiles;
+  P.plan = plan;
   P.variant = variant;
   P.host_teams = n_teams;
   P.host_blocks = n_blocks;
@@ -268,6 +268,11 @@ extern "C" int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens
   index->n_blocks = n_blocks;
   index->n_partials = n_partials;
   index->variant = variant;
-  index->reserved = (index->seg_tiles > 0 || getenv("PF_SEG_TILES")) ? 0 : seg_tiles;
+  int longest = plan.uniform;
+  if (plan.per_head) {
+    longest = 0;
+    for (int h = 0; h < pool->n_heads; ++h) longest = pf_max(longest, plan.of(h));
+  }
+  index->reserved = fixed ? 0 : longest;
   return PF_OK;
 }

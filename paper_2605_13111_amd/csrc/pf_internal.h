@@ -103,6 +103,14 @@ PF_HD PfHeadPlan pf_plan_head(int lkv, int seg_tiles) {
   hp.nseg = pf_max(1, pf_ceil_div(hp.n_kvt, seg_tiles));
   return hp;
 }
+// Segment lengths of a launch: one for every head, or one per head (small pools).
+constexpr int PF_PLAN_HEADS = 64;
+struct PfSegPlan {
+  int32_t uniform;                 // key tiles per work item when per_head == 0
+  int32_t per_head;
+  uint16_t seg[PF_PLAN_HEADS];
+  PF_HD int of(int h) const { return per_head ? (int)seg[h] : uniform; }
+};
 PF_HD int pf_seg_begin(int n_kvt, int nseg, int s) { return (int)(((long long)s * n_kvt) / nseg); }
 
 // One workgroup's job.  head < 0 = nothing to do.
@@ -128,7 +136,9 @@ struct __attribute__((aligned(64))) PfWorkHeader {
   int32_t pad[8];
 };
 
-// Layout of pf_index.work: header | counters[n_heads*n_qt] | head scratch[4*n_heads] | items[n_blocks]
+// Layout of pf_index.work: header | counters[n_heads*n_qt + PF_QUEUE_INTS] | head scratch[4*n_heads] | items[n_blocks]
+// (the last PF_QUEUE_INTS counters are the attention kernel's work-queue tickets)
+constexpr int PF_QUEUE_INTS = 16;
 struct PfWorkLayout {
   size_t counters_off, scratch_off, items_off, total;
 };
@@ -136,7 +146,7 @@ static inline size_t pf_align_up(size_t x, size_t a) { return (x + a - 1) / a * 
 static inline PfWorkLayout pf_work_layout(int n_heads, int n_qt, long long max_blocks) {
   PfWorkLayout L;
   L.counters_off = sizeof(PfWorkHeader);
-  L.scratch_off = pf_align_up(L.counters_off + sizeof(int32_t) * (size_t)n_heads * n_qt, 64);
+  L.scratch_off = pf_align_up(L.counters_off + sizeof(int32_t) * ((size_t)n_heads * n_qt + PF_QUEUE_INTS), 64);
   L.items_off = pf_align_up(L.scratch_off + sizeof(int32_t) * 4 * (size_t)n_heads, 64);
   L.total = L.items_off + sizeof(PfWorkItem) * (size_t)max_blocks;
   return L;
@@ -151,9 +161,10 @@ bool pf_chunk_layout_ok(const pf_chunk_layout *lay, int n_heads, int tokens, int
 int pf_resolve_seg_tiles(int seg_tiles);                   // 0 -> default, else clamped to the minimum
 int pf_resolve_variant(int head_dim);                      // kernel variant in use
 // Segment length that a host replay of the launch schedule finds best for this history length.
-int pf_auto_seg_tiles(const pf_pool *pool, int T, int q_tokens, int variant);
+void pf_auto_plan(const pf_pool *pool, int T, int q_tokens, int variant, bool queue, PfSegPlan *plan);
+bool pf_attn_queue_mode(int variant);                      // does this kernel take its blocks from the work queue?
 // Host plan for the pool's current T: per-launch block count and partial count.
-void pf_host_plan(const pf_pool *pool, int T, int q_tokens, int variant, int seg_tiles,
+void pf_host_plan(const pf_pool *pool, int T, int q_tokens, int variant, const PfSegPlan &plan,
                   int *n_teams, int *n_blocks, int *n_partials, int *max_sel_needed);
 
 #define PF_HIP_CHECK(expr)                         \
