@@ -370,6 +370,38 @@ def test_whole_chunk_from_a_hip_graph():
         assert torch.equal(getattr(index_e, name), getattr(index_g, name)), name
 
 
+def test_work_queue_and_one_block_per_workgroup_agree(monkeypatch):
+    """The pipelined kernel hands out its blocks through per-die queues (resident workgroups, stealing between
+    dies).  With the segment length fixed, that launch and the plain one-block-per-workgroup launch compute the
+    same blocks, so their outputs are equal bit for bit; so are repeated queue launches on one index (the tickets
+    are put back by the kernel itself).  A layer of the 30-layer step: about 2000 blocks for 256 workgroups."""
+    dev = "cuda:0"
+    w = synth.WORKLOADS["c3_step"]
+    H, D, tpf = w.n_heads, w.head_dim, w.tokens_per_frame
+    Lq = w.chunk_frames * tpf
+    pols = synth.policies("c3_step", layer=5)
+    pool = B.Pool(pols, tpf, D, device=dev)
+    B.pf_pool_reset(pool)
+    for ci in range(w.history_frames // 3):
+        B.pf_cache_append(pool, synth.randn_bf16((H, 3, tpf, D), 700 + ci, device=dev),
+                          synth.randn_bf16((H, 3, tpf, D), 730 + ci, device=dev), synth.frame_scores(H, 3, 760 + ci, device=dev))
+    q, kc, vc = [synth.randn_bf16((H, Lq, D), 790 + i, device=dev) for i in range(3)]
+    ws = torch.empty(B.pf_attn_workspace_bytes(pool, Lq), dtype=torch.uint8, device=dev)
+    index = B.Index(pool, Lq, seg_tiles=48)
+    B.pf_build_index(pool, index, Lq)
+    assert index.c.n_blocks > 1500
+    outs = []
+    for mode in ("1", "0", "1", "1"):
+        monkeypatch.setenv("PF_ATTN_QUEUE", mode)
+        o = torch.zeros((H, Lq, D), dtype=torch.bfloat16, device=dev)
+        B.pf_ragged_attn_fwd(pool, index, q, kc, vc, o, ws)
+        torch.cuda.synchronize()
+        outs.append(o)
+    for o in outs[1:]:
+        assert torch.equal(outs[0].view(torch.int16), o.view(torch.int16))
+    assert bool(torch.isfinite(outs[0].float()).all()) and float(outs[0].float().abs().max()) > 0
+
+
 def test_head_classification_matches_the_oracle():
     """Offline tri-pattern classification (Sec. 4.1): per-prompt types, periods and the voted head types of the
     kernel equal the oracle's exactly, on the synthetic sequences at the paper's sizes (30 x 12 heads, 69 history
