@@ -904,12 +904,18 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     }
   };
 
+  // A wave whose 32 query rows all lie beyond the chunk's end (the last query tile of a head) still sends its share
+  // of the copies and meets every barrier, but skips the fragments, MFMAs and softmax: its partner on the SIMD then
+  // has the issue slots to itself, and the matrix pipe does no work that is thrown away.
+  const bool has_rows = it.q0 + wave * 32 < P.q_tokens;
+
   // ---- matrix phase: PV of the tile whose V sits in stage st_pv (its fragments 0 .. PP_RING-1 already
   // requested), QK of the tile whose K sits in stage st_qk ----
   auto m_phase = [&](auto has_pv, auto has_qk, int st_qk, int st_pv, int st_v_next) {
     constexpr bool HAS_PV = decltype(has_pv)::value, HAS_QK = decltype(has_qk)::value;
     constexpr int FIRST = HAS_PV ? 0 : 16, LAST = HAS_QK ? 31 : 15;
     const unsigned offK = st_qk * PP_TILE_BYTES, offV = st_pv * PP_TILE_BYTES;
+    if (__builtin_expect(has_rows, 1)) {
     __builtin_amdgcn_s_setprio(3);                              // the matrix phase goes first on its SIMD
     if constexpr (!HAS_PV) static_for<16, 16 + PP_RING>([&](auto f) { issue_frag(f, offK, offV); });
     static_for<FIRST, LAST + 1>([&](auto f) {
@@ -924,6 +930,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     // end of the shorter of the two instruction streams
     if constexpr (HAS_QK) static_for<0, PP_RING>([&](auto f) { issue_frag(f, 0u, (unsigned)(st_v_next * PP_TILE_BYTES)); });
     __builtin_amdgcn_s_setprio(0);
+    }
     // this wave's rows of the tile after the QK tile (sent two vector phases ago) have landed once only the
     // copies of its last vector phase are outstanding
     if (HAS_QK) wait_copies(n_last);
@@ -953,6 +960,10 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
       }
     }
     plan_copy(kt + 4);
+    if (__builtin_expect(!has_rows, 0)) {
+      __builtin_amdgcn_s_barrier();
+      return;
+    }
     const int valid = H.lkv - kt * BK;                          // ragged tail: only the head's last tile
     if (__builtin_expect(valid < BK, 0)) {
 #pragma unroll
