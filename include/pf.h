@@ -226,6 +226,9 @@ int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens, void *str
  *   softmax_scale         0 = 1/sqrt(head_dim)
  *   workspace             dev, >= pf_attn_workspace_bytes(), 16-byte aligned
  * `index` must have been built for this q_tokens and the pool's current T.
+ * index->work (arrival counters, work-queue tickets) and the workspace are written
+ * by the launch and left ready for the next one: launches that share either must
+ * not overlap in time (same stream, or ordered by events).
  */
 int pf_ragged_attn_fwd(const pf_pool *pool, const pf_index *index,
                        const void *q, const void *k_cur, const void *v_cur, void *out,
@@ -233,8 +236,8 @@ int pf_ragged_attn_fwd(const pf_pool *pool, const pf_index *index,
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /* The same with q, k_cur, v_cur and out laid out by `layout` (one layout for all
- * four; q_tokens tokens).  layout must not be NULL.  Chunk key tiles are then
- * fetched row by row; history tiles are unaffected. */
+ * four; q_tokens tokens).  layout must not be NULL.  History tiles are unaffected;
+ * chunk tiles are fetched with the same 16-byte copies, one token row at a time. */
 int pf_ragged_attn_fwd_strided(const pf_pool *pool, const pf_index *index,
                                const void *q, const void *k_cur, const void *v_cur, void *out,
                                int q_tokens, float softmax_scale,

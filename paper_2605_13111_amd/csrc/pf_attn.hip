@@ -1,8 +1,10 @@
 // Ragged-cache attention forward (Sec. 4.3; Eq. 1 per head over [selected frames || chunk]).
 //
-// One launch per layer.  A workgroup owns BQ query rows of one head and a run of 64-key tiles of that
+// One launch per layer.  A work item is BQ query rows of one head and a run of 64-key tiles of that
 // head's ragged key sequence; heads with many keys are cut into several runs whose partial results are
-// merged by the last workgroup to finish (no spinning).  Two kernels share the operand layouts below:
+// merged by the last workgroup to finish (no spinning).  pf_attn_kernel runs one item per workgroup;
+// pf_attn_pp_kernel keeps one workgroup per compute unit resident and lets it take items from per-die queues
+// until all are empty.  Two kernels share the operand layouts below:
 //   pf_attn_kernel     BQ = 128, 4 waves x 32 query rows, two workgroups per CU, tiles staged through
 //                      registers into padded LDS rows; any head_dim in {64, 128}
 //   pf_attn_pp_kernel  BQ = 256, 8 waves x 32 query rows in two groups that alternate between a matrix phase
