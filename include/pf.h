@@ -180,6 +180,16 @@ size_t pf_attn_workspace_bytes(const pf_pool *pool, int q_tokens);
 int pf_selected_count(const pf_head_policy *pol, int T);
 int pf_retained_count(const pf_head_policy *pol, int T);
 
+/* The launch plan pf_build_index would make for the pool's policies at history
+ * length T (pool->T_host is not read) and a chunk of q_tokens tokens, with the
+ * library's own choice of segment lengths: seg_tiles[h] = 64-key tiles per work item
+ * of head h (>= its tile count when the head is not split), *n_blocks = work items
+ * of the launch, *n_partials = partial-result slots.  The same figures as the ones
+ * pf_index_work_bytes / pf_attn_workspace_bytes bound.  Host only; any pointer but
+ * pool may be NULL.  PF_OK or PF_ERR_INVALID_ARG. */
+int pf_plan_segments(const pf_pool *pool, int T, int q_tokens, int32_t *seg_tiles,
+                     int32_t *n_blocks, int32_t *n_partials);
+
 /* ---- the hot path -------------------------------------------------------- */
 
 /* Empty the pool: T = 0, n_frames = 0, frame_ids = -1, frame_score = 0,

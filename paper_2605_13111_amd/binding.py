@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "libpf.so")
 
 PF_OK, PF_ERR_INVALID_ARG, PF_ERR_CAPACITY, PF_ERR_UNSUPPORTED, PF_ERR_HIP = 0, -1, -2, -3, -4
 
-EXPORTS = ["pf_index_work_bytes", "pf_attn_workspace_bytes", "pf_selected_count", "pf_retained_count",
+EXPORTS = ["pf_index_work_bytes", "pf_attn_workspace_bytes", "pf_selected_count", "pf_retained_count", "pf_plan_segments",
            "pf_pool_reset", "pf_cache_append", "pf_cache_append_strided", "pf_build_index", "pf_ragged_attn_fwd",
            "pf_ragged_attn_fwd_strided", "pf_classify_heads", "pf_status_string"]
 
@@ -65,6 +65,8 @@ def lib():
         L.pf_selected_count.argtypes = [P(pf_head_policy), I]
         L.pf_retained_count.restype = I
         L.pf_retained_count.argtypes = [P(pf_head_policy), I]
+        L.pf_plan_segments.restype = I
+        L.pf_plan_segments.argtypes = [P(pf_pool), I, I, P(ctypes.c_int32), P(ctypes.c_int32), P(ctypes.c_int32)]
         L.pf_pool_reset.restype = I
         L.pf_pool_reset.argtypes = [P(pf_pool), V]
         L.pf_cache_append.restype = I
@@ -115,6 +117,15 @@ def make_policy(p):
 def pf_selected_count(policy, T):
     c = make_policy(policy)
     return int(lib().pf_selected_count(ctypes.byref(c), int(T)))
+
+
+def pf_plan_segments(pool_c, T, q_tokens):
+    """(seg_tiles per head, n_blocks, n_partials) of the launch plan for history length T; pool_c is a pf_pool struct."""
+    seg = (ctypes.c_int32 * pool_c.n_heads)()
+    nb, npart = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().pf_plan_segments(ctypes.byref(pool_c), int(T), int(q_tokens), seg, ctypes.byref(nb), ctypes.byref(npart)),
+           "pf_plan_segments")
+    return list(seg), nb.value, npart.value
 
 
 def pf_retained_count(policy, T):

@@ -145,7 +145,7 @@ static double model_finish(const std::vector<int> &n_kvt, const std::vector<int>
 
 namespace {
 struct PlanEntry {
-  std::vector<int> key;                              // n_kvt of every head, then n_qt, kernel and mode
+  std::vector<int> key;                              // n_kvt of every head, then n_qt, then kernel, launch form and planning depth
   PfSegPlan plan;
 };
 std::mutex g_plan_mutex;
@@ -170,7 +170,8 @@ void pf_auto_plan(const pf_pool *pool, int T, int q_tokens, int variant, bool qu
 
   std::vector<int> key(n_kvt);
   key.push_back(n_qt);
-  key.push_back(variant * 2 + (queue ? 1 : 0));
+  const bool uniform_only = H > PF_PLAN_HEADS || getenv("PF_PLAN_UNIFORM") != nullptr;
+  key.push_back(variant * 4 + (queue ? 2 : 0) + (uniform_only ? 1 : 0));
   {
     std::lock_guard<std::mutex> lock(g_plan_mutex);
     for (size_t i = 0; i < g_plan_cache.size(); ++i)
@@ -195,7 +196,7 @@ void pf_auto_plan(const pf_pool *pool, int T, int q_tokens, int variant, bool qu
   const double uniform_t = model_finish(n_kvt, seg, n_qt, slots_per_die, queue);
 
   // step 2: per key count, the segment count of its own
-  if (H <= PF_PLAN_HEADS && !getenv("PF_PLAN_UNIFORM")) {
+  if (!uniform_only) {
     std::vector<int> distinct(n_kvt);
     std::sort(distinct.begin(), distinct.end());
     distinct.erase(std::unique(distinct.begin(), distinct.end()), distinct.end());
@@ -317,6 +318,28 @@ extern "C" size_t pf_attn_workspace_bytes(const pf_pool *pool, int q_tokens) {
     need = t > need ? t : need;
   }
   return pf_align_up(need + 256, 256);
+}
+
+extern "C" int pf_plan_segments(const pf_pool *pool, int T, int q_tokens, int32_t *seg_tiles, int32_t *n_blocks,
+                                int32_t *n_partials) {
+  if (pf_validate_pool(pool) != PF_OK || T < 0 || q_tokens < 1 || q_tokens > (1 << 24)) return PF_ERR_INVALID_ARG;
+  for (int h = 0; h < pool->n_heads; ++h)
+    if (pf_sel_count_impl(pool->policy_host[h], T) > pool->policy_host[h].slots) return PF_ERR_INVALID_ARG;
+  const int variant = pf_resolve_variant(pool->head_dim);
+  PfSegPlan plan;
+  if (getenv("PF_SEG_TILES")) {
+    memset(&plan, 0, sizeof(plan));
+    plan.uniform = pf_resolve_seg_tiles(0);
+  } else {
+    pf_auto_plan(pool, T, q_tokens, variant, pf_attn_queue_mode(variant), &plan);
+  }
+  int teams, blocks, partials, max_sel;
+  pf_host_plan(pool, T, q_tokens, variant, plan, &teams, &blocks, &partials, &max_sel);
+  if (seg_tiles)
+    for (int h = 0; h < pool->n_heads; ++h) seg_tiles[h] = plan.of(h);
+  if (n_blocks) *n_blocks = blocks;
+  if (n_partials) *n_partials = partials;
+  return PF_OK;
 }
 
 extern "C" int pf_selected_count(const pf_head_policy *pol, int T) {

@@ -155,3 +155,52 @@ def test_classify_argument_validation_without_a_device():
     assert call(fake, 2, 3, 10, 1.5, 6.4, fake, fake) == B.PF_ERR_INVALID_ARG
     assert call(fake, 2, 3, 10, 0.8, -1.0, fake, fake) == B.PF_ERR_INVALID_ARG
     assert call(fake, 2, 3, 2000, 0.8, 6.4, fake, fake) == B.PF_ERR_UNSUPPORTED
+
+
+def _tiles(pol, T, tpf, q_tokens):
+    return -(-(B.pf_selected_count(pol, T) * tpf + q_tokens) // 64)
+
+
+def test_launch_plan_stays_inside_the_advertised_buffers(monkeypatch):
+    """pf_plan_segments (host only) returns the plan pf_build_index would launch.  For the bench workload's drawn
+    policies at several history lengths, in both launch forms and with the per-head step switched off: every split
+    head's segments are at least 48 tiles long, the block and partial counts follow from the segment lengths, and
+    they fit what pf_index_work_bytes / pf_attn_workspace_bytes promise for any history length."""
+    w = synth.WORKLOADS["c3_step"]
+    tpf, D, Lq = w.tokens_per_frame, w.head_dim, w.chunk_frames * w.tokens_per_frame
+    n_qt = -(-Lq // 256)
+    for layer in (0, 7, 13):
+        pols = synth.policies("c3_step", layer=layer)
+        pool = _fake_pool(pols, tpf=tpf, D=D)
+        work_bytes = B.lib().pf_index_work_bytes(ctypes.byref(pool), Lq)
+        ws_bytes = B.lib().pf_attn_workspace_bytes(ctypes.byref(pool), Lq)
+        for env in ({}, {"PF_ATTN_QUEUE": "0"}, {"PF_PLAN_UNIFORM": "1"}):
+            for k in ("PF_ATTN_QUEUE", "PF_PLAN_UNIFORM"):
+                monkeypatch.delenv(k, raising=False)
+            for k, v in env.items():
+                monkeypatch.setenv(k, v)
+            for T in (0, 3, 21, 57):
+                seg, n_blocks, n_partials = B.pf_plan_segments(pool, T, Lq)
+                assert B.pf_plan_segments(pool, T, Lq) == (seg, n_blocks, n_partials)       # remembered, same answer
+                teams = parts = 0
+                for pol, sg in zip(pols, seg):
+                    n = _tiles(pol, T, tpf, Lq)
+                    nseg = max(1, -(-n // sg))
+                    assert sg >= 48 or nseg == 1, (layer, T, sg, n)
+                    teams += nseg
+                    parts += nseg * n_qt if nseg > 1 else 0
+                assert n_blocks == -(-teams // 8) * 8 * n_qt and n_partials == parts
+                assert n_partials * 256 * (D + 2) * 4 <= ws_bytes
+                assert 64 + 4 * (len(pols) * n_qt + 16) + 16 * len(pols) + 32 * n_blocks <= work_bytes
+                if env.get("PF_PLAN_UNIFORM"):
+                    assert len(set(seg)) == 1
+
+
+def test_launch_plan_rejects_bad_arguments():
+    pool = _fake_pool([synth.anchor_all(4), synth.veil(1, 2)], tpf=1560, D=128)
+    lib = B.lib()
+    assert lib.pf_plan_segments(None, 3, 4680, None, None, None) == B.PF_ERR_INVALID_ARG
+    assert lib.pf_plan_segments(ctypes.byref(pool), -1, 4680, None, None, None) == B.PF_ERR_INVALID_ARG
+    assert lib.pf_plan_segments(ctypes.byref(pool), 3, 0, None, None, None) == B.PF_ERR_INVALID_ARG
+    assert lib.pf_plan_segments(ctypes.byref(pool), 9, 4680, None, None, None) == B.PF_ERR_INVALID_ARG   # 9 frames > 4 slots
+    assert lib.pf_plan_segments(ctypes.byref(pool), 3, 4680, None, None, None) == B.PF_OK
