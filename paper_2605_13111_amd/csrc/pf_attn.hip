@@ -625,6 +625,7 @@ __device__ __forceinline__ int pp_copy_rows_slow(int kt, const HeadKV &H, char *
   typedef __attribute__((address_space(3))) void *lptr_t;
   constexpr int D = 128;
   const int last = H.lkv - 1 - kt * PF_BK;
+  asm volatile("" : "+v"(lane));                    // rare path: its per-lane offsets are worked out here, not held in registers through the loop
 #pragma unroll
   for (int r = 0; r < 8; ++r) {
     const int row = wave * 8 + r;
@@ -968,11 +969,13 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     }
     const int valid = H.lkv - kt * BK;                          // ragged tail: only the head's last tile
     if (__builtin_expect(valid < BK, 0)) {
+      int g_l = g;
+      asm volatile("" : "+v"(g_l));                              // rare path: its per-lane constants are not held in registers
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-          if (kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3) >= valid) s[kb][i] = -INFINITY;
+          if (kb * 32 + 8 * (i >> 2) + 4 * g_l + (i & 3) >= valid) s[kb][i] = -INFINITY;
     }
     float mx = s[0][0];
 #pragma unroll
