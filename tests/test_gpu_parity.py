@@ -402,6 +402,15 @@ def test_work_queue_and_one_block_per_workgroup_agree(monkeypatch):
     assert bool(torch.isfinite(outs[0].float()).all()) and float(outs[0].float().abs().max()) > 0
 
 
+def test_more_heads_than_the_per_head_planner_takes():
+    """72 heads in one pool (all layers' heads of a small model in one launch): beyond 64 heads the launch plan uses
+    one segment length for all heads; pool, index and attention as in the other cases."""
+    pols = _mixed(12) * 9
+    assert len(pols) == 72
+    a, r = G.run_case(pols, 24, 128, [3, 3, 3, 3], 72, seed=61, label="72 heads")
+    print("72 heads max-abs %.2e rel %.2e" % (a, r))
+
+
 def test_head_classification_matches_the_oracle():
     """Offline tri-pattern classification (Sec. 4.1): per-prompt types, periods and the voted head types of the
     kernel equal the oracle's exactly, on the synthetic sequences at the paper's sizes (30 x 12 heads, 69 history
