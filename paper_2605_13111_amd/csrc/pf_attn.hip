@@ -656,11 +656,15 @@ __device__ __forceinline__ void pp_issue_frag(u32x2 (&vl)[16], u32x2 (&vh)[16], 
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(kf[J]) : "v"(a), "n"((J & 1) * 8192));
   }
 }
+// The wait is the compiler's own instruction fenced on both sides, not an asm statement tied to the fragment's
+// registers: after an asm statement that writes a register the compiler puts a wait state in front of the MFMA
+// that reads it (one issue slot per MFMA).
 template <int I, int LAST>
 __device__ __forceinline__ void pp_wait_frag(u32x2 (&vl)[16], u32x2 (&vh)[16], u32x4 (&kf)[16]) {
   constexpr int N = pp_reads_between(I, LAST) > 15 ? 15 : pp_reads_between(I, LAST);
-  if constexpr (I < 16) asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(vl[I]), "+v"(vh[I]) : "n"(N));
-  else asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(kf[I - 16]) : "n"(N));
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8));                 // lgkmcnt(N), the other counters untouched
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 template <int D>
