@@ -210,9 +210,8 @@ def main():
     # ---------------------------------------------------------------- cpu_baseline: the oracle on a bounded sample
     if not args.no_cpu:
         from oracle import attention as OA
+        from oracle import check as G
         from oracle.pool import PoolOracle
-        sys.path.insert(0, os.path.join(ROOT, "tests"))
-        import gpu_common as G
         pols, keep_k, keep_v, keep_s = hist0
         pool_o = PoolOracle(pols, tpf, D)
         for k_new, v_new, sc in zip(keep_k, keep_v, keep_s):
@@ -226,7 +225,7 @@ def main():
         want = G.oracle_attention(pool_o, sel_count, sel_frames, qc, kc, vc, rows=rows)
         cpu_s = time.perf_counter() - t0
         cpu_flops = sum(4.0 * len(rows) * (int(n) * tpf + Lq) * D for n in sel_count)
-        worst_abs, worst_rel = G.compare_attention(out, want, rows=rows, label="bench layer 0")
+        worst_abs, worst_rel = G.compare_attention(out.float().cpu().numpy(), want, rows=rows, label="bench layer 0")
         result["cpu_baseline"] = {"value": round(cpu_flops / cpu_s / 1e12, 6), "unit": "TFLOP/s",
                                   "cores": OA.num_threads(), "kind": "oracle",
                                   "sample": "layer 0, all %d heads, %d seeded query rows per head (%.1f GFLOP effective, "
@@ -262,7 +261,7 @@ def stream_bench(args, B, synth, dev):
     passes = 4
     layers = []
     for layer in range(n_layers):
-        pols = synth.policies(w.name, layer=layer)
+        pols = synth.policies(w.name, layer=layer, slots_of=lambda p: B.slots_needed(p, w.history_frames))
         pool = B.Pool(pols, tpf, D, device=dev)
         index = B.Index(pool, Lq)
         q = synth.randn_bf16((H, Lq, D), 900000 + layer, device=dev)

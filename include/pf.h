@@ -78,6 +78,7 @@ extern "C" {
  * head's region of the pool.
  */
 #define PF_MERGED_FRAME (1 << 30)
+#define PF_SYNC_STRIDE 32          /* int32 words between the per-head counters of pf_pool.sync (128 bytes) */
 typedef struct pf_head_policy {
   int32_t type;      /* PF_ANCHOR | PF_WAVE | PF_VEIL */
   int32_t mode;      /* PF_MODE_*, Anchor only (0 otherwise) */
@@ -113,7 +114,8 @@ typedef struct pf_pool {
   int32_t *frame_ids;             /* dev [total_slots]  global frame id, -1 = free */
   float   *frame_score;           /* dev [total_slots]  score of the resident frame, 0 = free */
   int32_t *T_dev;                 /* dev [1]            frames appended so far */
-  int32_t *sync;                  /* dev [n_heads]      library scratch, zeroed by pf_pool_reset */
+  int32_t *sync;                  /* dev [n_heads * PF_SYNC_STRIDE] library scratch (one arrival counter per head,
+                                     each in a cache line of its own), zeroed by pf_pool_reset */
   int32_t T_host;                 /* [lib] host mirror of *T_dev (no device read-back needed) */
   int32_t reserved;
 } pf_pool;
@@ -142,7 +144,7 @@ typedef struct pf_index {
   int32_t n_blocks;               /* workgroups of the attention launch */
   int32_t n_partials;             /* partial-result slots the launch uses */
   int32_t variant;                /* kernel variant the plan was built for */
-  int32_t reserved;               /* longest segment length the library planned (0 when the caller fixed it); start at 0 */
+  int32_t longest_seg;            /* longest segment (64-key tiles per work item) the library planned; 0 when the caller fixed seg_tiles */
 } pf_index;
 
 /*
@@ -190,10 +192,21 @@ int pf_retained_count(const pf_head_policy *pol, int T);
 int pf_plan_segments(const pf_pool *pool, int T, int q_tokens, int32_t *seg_tiles,
                      int32_t *n_blocks, int32_t *n_partials);
 
+/* Process-wide tuning switches, for tests and A/B measurements.  Each argument: -1 = leave unchanged.
+ *   attn_variant  attention kernel for head_dim 128: 0 = 4 waves x 32 query rows, staged through registers;
+ *                 1 = 8 waves x 32 rows in two alternating groups (the default)
+ *   attn_queue    1 = resident workgroups fed from per-die work queues (default), 0 = one work item per workgroup
+ *   seg_tiles     key tiles per work item for every head, 0 = planned per launch (default)
+ *   plan_uniform  1 = the planner stops after choosing one segment length for all heads
+ * The initial values come from the environment variables PF_ATTN_VARIANT, PF_ATTN_QUEUE, PF_SEG_TILES and
+ * PF_PLAN_UNIFORM, read once at the library's first use.  Takes effect at the next pf_build_index (and the size
+ * queries); an index must be rebuilt after a change.  Not synchronised with calls running on other threads. */
+int pf_set_tuning(int attn_variant, int attn_queue, int seg_tiles, int plan_uniform);
+
 /* ---- the hot path -------------------------------------------------------- */
 
 /* Empty the pool: T = 0, n_frames = 0, frame_ids = -1, frame_score = 0,
- * sync = 0.  K/V bytes are left as they are. */
+ * sync = 0 (all n_heads * PF_SYNC_STRIDE words).  K/V bytes are left as they are. */
 int pf_pool_reset(pf_pool *pool, void *stream);
 
 /*
@@ -205,7 +218,9 @@ int pf_pool_reset(pf_pool *pool, void *stream);
  *   scores        dev [n_heads][n_new] float, or NULL (= 0) -- used by Anchor/TOPK
  * PF_ERR_CAPACITY if any head would hold more than its `slots` frames after
  * eviction, or if a head's resident frames plus n_new exceed 1024 (the kernel's
- * per-head tables); the pool is then untouched.  On success pool->T_host += n_new.
+ * per-head tables); PF_ERR_UNSUPPORTED if n_heads x the largest Veil merge capacity exceeds
+ * 65535 (the merge launch's grid).  The pool is then untouched: every check happens before
+ * the first launch.  On success pool->T_host += n_new.
  */
 int pf_cache_append(pf_pool *pool, const void *k_new, const void *v_new,
                     int n_new, const float *scores, void *stream);
@@ -224,6 +239,13 @@ int pf_cache_append_strided(pf_pool *pool, const void *k_new, const void *v_new,
  * PF_ERR_CAPACITY if a head selects more than max_sel frames.
  */
 int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens, void *stream);
+
+/* Device address of the index's status word (one int32 inside index->work), written by pf_build_index's kernel:
+ * 0 = the selection found on the device agrees with the launch plan the host made from the policies' closed-form
+ * counts; non-zero = it does not (the pool was not filled through pf_cache_append, or tables were overwritten), the
+ * plan is then left empty and pf_ragged_attn_fwd on this index writes nothing to `out`.  A caller that cannot
+ * rule this out reads the word after the stream has run the build.  NULL on a bad argument. */
+const int32_t *pf_index_status_dev(const pf_index *index);
 
 /*
  * Ragged-cache attention (Sec. 4.3) = Eq. 1 evaluated per head over that

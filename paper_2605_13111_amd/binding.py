@@ -13,10 +13,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libpf.so")
 
 PF_OK, PF_ERR_INVALID_ARG, PF_ERR_CAPACITY, PF_ERR_UNSUPPORTED, PF_ERR_HIP = 0, -1, -2, -3, -4
+PF_SYNC_STRIDE = 32            # int32 words between the per-head counters of pf_pool.sync
 
 EXPORTS = ["pf_index_work_bytes", "pf_attn_workspace_bytes", "pf_selected_count", "pf_retained_count", "pf_plan_segments",
            "pf_pool_reset", "pf_cache_append", "pf_cache_append_strided", "pf_build_index", "pf_ragged_attn_fwd",
-           "pf_ragged_attn_fwd_strided", "pf_classify_heads", "pf_status_string"]
+           "pf_ragged_attn_fwd_strided", "pf_classify_heads", "pf_status_string", "pf_set_tuning", "pf_index_status_dev"]
 
 
 class pf_head_policy(ctypes.Structure):
@@ -42,7 +43,7 @@ class pf_index(ctypes.Structure):
                 ("sel_count", ctypes.c_void_p), ("sel_frames", ctypes.c_void_p), ("sel_slots", ctypes.c_void_p),
                 ("cu_seqlens", ctypes.c_void_p), ("work", ctypes.c_void_p), ("work_bytes", ctypes.c_size_t),
                 ("q_tokens", ctypes.c_int32), ("T_built", ctypes.c_int32), ("n_blocks", ctypes.c_int32),
-                ("n_partials", ctypes.c_int32), ("variant", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("n_partials", ctypes.c_int32), ("variant", ctypes.c_int32), ("longest_seg", ctypes.c_int32)]
 
 
 _lib = None
@@ -82,6 +83,10 @@ def lib():
                                                  P(pf_chunk_layout), V]
         L.pf_classify_heads.restype = I
         L.pf_classify_heads.argtypes = [V, I, I, I, ctypes.c_double, ctypes.c_double, V, V, V, V]
+        L.pf_set_tuning.restype = I
+        L.pf_set_tuning.argtypes = [I, I, I, I]
+        L.pf_index_status_dev.restype = V
+        L.pf_index_status_dev.argtypes = [P(pf_index)]
         L.pf_status_string.restype = ctypes.c_char_p
         L.pf_status_string.argtypes = [I]
         _lib = L
@@ -114,6 +119,19 @@ def make_policy(p):
                           int(p.slots), 0)
 
 
+def pf_set_tuning(attn_variant=-1, attn_queue=-1, seg_tiles=-1, plan_uniform=-1):
+    """Process-wide tuning switches; -1 leaves a switch unchanged."""
+    _check(lib().pf_set_tuning(int(attn_variant), int(attn_queue), int(seg_tiles), int(plan_uniform)), "pf_set_tuning")
+
+
+def pf_index_status(index):
+    """The index's device status word as a Python int (synchronises): 0 = the plan is valid."""
+    addr = lib().pf_index_status_dev(ctypes.byref(index.c))
+    off = addr - index.work.data_ptr()
+    torch.cuda.synchronize()
+    return int(index.work[off:off + 4].view(torch.int32).item())
+
+
 def pf_selected_count(policy, T):
     c = make_policy(policy)
     return int(lib().pf_selected_count(ctypes.byref(c), int(T)))
@@ -131,6 +149,14 @@ def pf_plan_segments(pool_c, T, q_tokens):
 def pf_retained_count(policy, T):
     c = make_policy(policy)
     return int(lib().pf_retained_count(ctypes.byref(c), int(T)))
+
+
+def slots_needed(policy, max_T):
+    """Pool capacity (frames) that keeps pf_cache_append within bounds for history lengths up to max_T: the
+    library's closed-form retained count at its largest, plus one slot per merged frame of a Veil head."""
+    big = policy._replace(slots=1 << 20)
+    need = max(pf_retained_count(big, T) for T in range(max_T + 1))
+    return need + (int(policy.cap) if int(policy.type) == 2 and int(policy.cap) > 0 else 0)
 
 
 class Pool:
@@ -160,7 +186,7 @@ class Pool:
         self.frame_ids = torch.full((total,), -1, dtype=torch.int32, device=dev)
         self.frame_score = torch.zeros(total, dtype=torch.float32, device=dev)
         self.T_dev = torch.zeros(1, dtype=torch.int32, device=dev)
-        self.sync = torch.zeros(H, dtype=torch.int32, device=dev)
+        self.sync = torch.zeros(H * PF_SYNC_STRIDE, dtype=torch.int32, device=dev)
         self.c = pf_pool(H, self.D, self.tpf, 0, total, self.k_pool.data_ptr(), self.v_pool.data_ptr(),
                          ctypes.cast(self.host_policy, ctypes.POINTER(pf_head_policy)), self.policy_dev.data_ptr(),
                          self.slot_base.data_ptr(), self.n_frames.data_ptr(), self.frame_ids.data_ptr(),

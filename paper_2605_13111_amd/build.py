@@ -39,17 +39,5 @@ def build(verbose=False, extra=()):
     return LIB
 
 
-def build_ubench():
-    """The stand-alone micro-benchmarks (pf_ubench.hip); not needed by the library, the tests or the bench."""
-    exe = os.path.join(HERE, "pf_ubench")
-    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang",
-                           "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-                           os.path.join(CSRC, "pf_ubench.hip"), "-o", exe])
-    return exe
-
-
 if __name__ == "__main__":
-    if "--ubench" in sys.argv:
-        print(build_ubench())
-    else:
-        print(build(verbose=True))
+    print(build(verbose=True))

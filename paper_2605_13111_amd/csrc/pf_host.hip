@@ -5,6 +5,7 @@
 #include <functional>
 #include <mutex>
 #include <queue>
+#include <unordered_map>
 #include <vector>
 #include "pf_internal.h"
 
@@ -42,10 +43,39 @@ int pf_validate_pool(const pf_pool *pool) {
   return PF_OK;
 }
 
+// ---- process-wide tuning switches ---------------------------------------------------------------
+// Defaults come from the environment (PF_ATTN_VARIANT, PF_ATTN_QUEUE, PF_SEG_TILES, PF_PLAN_UNIFORM), read once at
+// first use; pf_set_tuning changes them afterwards.  Plain ints: a change races with calls running on other threads.
+namespace {
+struct Tuning {
+  int attn_variant, attn_queue, seg_tiles, plan_uniform;
+};
+int env_int(const char *name, int dflt) {
+  const char *e = getenv(name);
+  return e ? atoi(e) : dflt;
+}
+Tuning &tuning() {
+  static Tuning t = {env_int("PF_ATTN_VARIANT", PF_DEFAULT_VARIANT), env_int("PF_ATTN_QUEUE", 1),
+                     env_int("PF_SEG_TILES", 0), getenv("PF_PLAN_UNIFORM") ? 1 : 0};
+  return t;
+}
+}  // namespace
+
+extern "C" int pf_set_tuning(int attn_variant, int attn_queue, int seg_tiles, int plan_uniform) {
+  if (attn_variant >= PF_NUM_VARIANTS || seg_tiles > (1 << 20)) return PF_ERR_INVALID_ARG;
+  Tuning &t = tuning();
+  if (attn_variant >= 0) t.attn_variant = attn_variant;
+  if (attn_queue >= 0) t.attn_queue = attn_queue != 0;
+  if (seg_tiles >= 0) t.seg_tiles = seg_tiles;
+  if (plan_uniform >= 0) t.plan_uniform = plan_uniform != 0;
+  return PF_OK;
+}
+
+int pf_tuned_seg_tiles() { return tuning().seg_tiles > 0 ? tuning().seg_tiles : 0; }
+
 int pf_resolve_seg_tiles(int seg_tiles) {
   if (seg_tiles <= 0) {
-    const char *e = getenv("PF_SEG_TILES");
-    seg_tiles = e ? atoi(e) : 0;
+    seg_tiles = pf_tuned_seg_tiles();
     if (seg_tiles <= 0) seg_tiles = PF_DEFAULT_SEG_TILES;
   }
   return seg_tiles < PF_MIN_SEG_TILES ? PF_MIN_SEG_TILES : seg_tiles;
@@ -65,8 +95,8 @@ int pf_resolve_seg_tiles(int seg_tiles) {
 //   1. one segment length for every head, from a list of candidates;
 //   2. starting from that, heads with the same key count try every segment count of their own while the
 //      others stay fixed, a few rounds (pools of up to PF_PLAN_HEADS heads).
-// Plans are remembered per (key tiles of every head, query tiles, kernel, mode), so a steady-state step pays a
-// table lookup.
+// Plans are remembered per (key tiles of every head, query tiles, kernel, mode) in a hash table large enough for
+// whole rollouts, so a step whose shape has been seen before pays a lookup.
 static const int kSegCandidates[] = {48, 56, 64, 72, 80, 96, 112, 128, 144, 160, 176, 192, 224, 256, 320, 384};
 constexpr int PF_AUTO_MIN_SEG = 48;                 // shortest planned segment: bounds the partial-result workspace
 struct PlanCosts {
@@ -77,7 +107,7 @@ static const PlanCosts kCostsQueue = {4.0, 2.0, 3.0};
 constexpr int PF_PLAN_ROUNDS = 3;
 constexpr int PF_PLAN_MAX_NSEG = 16;                // segment counts tried per head in step 2
 constexpr double PF_PLAN_MIN_GAIN = 0.01;           // step 2 must beat step 1 by this much to be used
-constexpr size_t PF_PLAN_CACHE = 256;
+constexpr size_t PF_PLAN_CACHE = 16384;            // remembered plans (about 300 bytes each)
 
 // Finish time of the launch in which head h has key tiles n_kvt[h] cut into segments of at most seg[h] tiles.
 static double model_finish(const std::vector<int> &n_kvt, const std::vector<int> &seg, int n_qt, int slots_per_die,
@@ -144,13 +174,17 @@ static double model_finish(const std::vector<int> &n_kvt, const std::vector<int>
 }
 
 namespace {
-struct PlanEntry {
-  std::vector<int> key;                              // n_kvt of every head, then n_qt, then kernel, launch form and planning depth
-  PfSegPlan plan;
+// Remembered plans: key = key tiles of every head, then query tiles, then kernel / launch form / planning depth.
+// Sized for whole rollouts (30 layers x a few hundred history lengths each have their own key); emptied when full.
+struct KeyHash {
+  size_t operator()(const std::vector<int> &k) const {
+    unsigned long long h = 1469598103934665603ull;
+    for (size_t i = 0; i < k.size(); ++i) h = (h ^ (unsigned)k[i]) * 1099511628211ull;
+    return (size_t)h;
+  }
 };
 std::mutex g_plan_mutex;
-std::vector<PlanEntry> g_plan_cache;
-size_t g_plan_next = 0;
+std::unordered_map<std::vector<int>, PfSegPlan, KeyHash> g_plan_cache;
 }  // namespace
 
 void pf_auto_plan(const pf_pool *pool, int T, int q_tokens, int variant, bool queue, PfSegPlan *plan) {
@@ -159,41 +193,52 @@ void pf_auto_plan(const pf_pool *pool, int T, int q_tokens, int variant, bool qu
   const int slots_per_die = 32 * (variant == 0 ? 2 : 1);          // workgroups resident per die
   memset(plan, 0, sizeof(*plan));
   plan->uniform = PF_DEFAULT_SEG_TILES;
-  std::vector<int> n_kvt(H);
+  std::vector<int> key(H + 2);
   long long total = 0;
   for (int h = 0; h < H; ++h) {
     const int nsel = pf_sel_count_impl(pool->policy_host[h], T);
-    n_kvt[h] = pf_ceil_div(nsel * pool->tokens_per_frame + q_tokens, PF_BK);
-    total += pf_ceil_div(n_kvt[h], PF_AUTO_MIN_SEG);
+    key[h] = pf_ceil_div(nsel * pool->tokens_per_frame + q_tokens, PF_BK);
+    total += pf_ceil_div(key[h], PF_AUTO_MIN_SEG);
   }
   if (total * n_qt > 50000) return;                               // keep the replay cheap on huge launches
-
-  std::vector<int> key(n_kvt);
-  key.push_back(n_qt);
-  const bool uniform_only = H > PF_PLAN_HEADS || getenv("PF_PLAN_UNIFORM") != nullptr;
-  key.push_back(variant * 4 + (queue ? 2 : 0) + (uniform_only ? 1 : 0));
+  const bool uniform_only = H > PF_PLAN_HEADS || tuning().plan_uniform != 0;
+  key[H] = n_qt;
+  key[H + 1] = variant * 4 + (queue ? 2 : 0) + (uniform_only ? 1 : 0);
   {
     std::lock_guard<std::mutex> lock(g_plan_mutex);
-    for (size_t i = 0; i < g_plan_cache.size(); ++i)
-      if (g_plan_cache[i].key == key) {
-        *plan = g_plan_cache[i].plan;
-        return;
-      }
+    auto hit = g_plan_cache.find(key);
+    if (hit != g_plan_cache.end()) {
+      *plan = hit->second;
+      return;
+    }
   }
+  const std::vector<int> n_kvt(key.begin(), key.begin() + H);
+
+  // Many candidate lengths cut the heads into the same segment counts: the replay runs once per distinct cut.
+  std::unordered_map<std::vector<int>, double, KeyHash> seen;
+  std::vector<int> cut(H);
+  auto finish_of = [&](const std::vector<int> &seg) {
+    for (int h = 0; h < H; ++h) cut[h] = pf_max(1, pf_ceil_div(n_kvt[h], seg[h]));
+    auto f = seen.find(cut);
+    if (f != seen.end()) return f->second;
+    const double t = model_finish(n_kvt, seg, n_qt, slots_per_die, queue);
+    seen.emplace(cut, t);
+    return t;
+  };
 
   // step 1: one length for all
   std::vector<int> seg(H);
   double best_t = 0.0;
   for (size_t ci = 0; ci < sizeof(kSegCandidates) / sizeof(kSegCandidates[0]); ++ci) {
     std::fill(seg.begin(), seg.end(), kSegCandidates[ci]);
-    const double t = model_finish(n_kvt, seg, n_qt, slots_per_die, queue);
+    const double t = finish_of(seg);
     if (best_t == 0.0 || t < best_t * 0.995) {       // a longer segment must win clearly: it costs fewer partials
       best_t = best_t == 0.0 ? t : (t < best_t ? t : best_t);
       plan->uniform = kSegCandidates[ci];
     }
   }
   std::fill(seg.begin(), seg.end(), plan->uniform);
-  const double uniform_t = model_finish(n_kvt, seg, n_qt, slots_per_die, queue);
+  const double uniform_t = finish_of(seg);
 
   // step 2: per key count, the segment count of its own
   if (!uniform_only) {
@@ -215,7 +260,7 @@ void pf_auto_plan(const pf_pool *pool, int T, int q_tokens, int variant, bool qu
           if (cand == cur_seg) continue;
           for (int h = 0; h < H; ++h)
             if (n_kvt[h] == nk) seg[h] = pf_max(cand, PF_AUTO_MIN_SEG);
-          const double t = model_finish(n_kvt, seg, n_qt, slots_per_die, queue);
+          const double t = finish_of(seg);
           if (t < cur_t * 0.998) {
             cur_t = t;
             best_seg = pf_max(cand, PF_AUTO_MIN_SEG);
@@ -234,27 +279,16 @@ void pf_auto_plan(const pf_pool *pool, int T, int q_tokens, int variant, bool qu
   }
 
   std::lock_guard<std::mutex> lock(g_plan_mutex);
-  PlanEntry e;
-  e.key = key;
-  e.plan = *plan;
-  if (g_plan_cache.size() < PF_PLAN_CACHE) {
-    g_plan_cache.push_back(e);
-  } else {
-    g_plan_cache[g_plan_next] = e;
-    g_plan_next = (g_plan_next + 1) % PF_PLAN_CACHE;
-  }
+  if (g_plan_cache.size() >= PF_PLAN_CACHE) g_plan_cache.clear();
+  g_plan_cache.emplace(key, *plan);
 }
 
-bool pf_attn_queue_mode(int variant) {
-  const char *e = getenv("PF_ATTN_QUEUE");
-  return variant == 1 && !(e && atoi(e) == 0);
-}
+bool pf_attn_queue_mode(int variant) { return variant >= 1 && tuning().attn_queue != 0; }
 
 int pf_resolve_variant(int head_dim) {
-  const char *e = getenv("PF_ATTN_VARIANT");
-  int v = e ? atoi(e) : PF_DEFAULT_VARIANT;
+  int v = tuning().attn_variant;
   if (v < 0 || v >= PF_NUM_VARIANTS) v = PF_DEFAULT_VARIANT;
-  return head_dim == 128 ? v : 0;                   // kernel 1 exists for head_dim 128 only
+  return head_dim == 128 ? v : 0;                   // the pipelined kernels exist for head_dim 128 only
 }
 
 void pf_host_plan(const pf_pool *pool, int T, int q_tokens, int variant, const PfSegPlan &plan,
@@ -313,7 +347,7 @@ extern "C" size_t pf_attn_workspace_bytes(const pf_pool *pool, int q_tokens) {
   for (int v = 0; v < PF_NUM_VARIANTS; ++v) {
     long long mb, mp;
     int n_qt;
-    worst_case(pool, q_tokens, getenv("PF_SEG_TILES") ? pf_resolve_seg_tiles(0) : PF_AUTO_MIN_SEG, v, &mb, &mp, &n_qt);
+    worst_case(pool, q_tokens, pf_tuned_seg_tiles() ? pf_resolve_seg_tiles(0) : PF_AUTO_MIN_SEG, v, &mb, &mp, &n_qt);
     const size_t t = (size_t)mp * pf_partial_bytes(pf_variant_bq(v), pool->head_dim);
     need = t > need ? t : need;
   }
@@ -327,7 +361,7 @@ extern "C" int pf_plan_segments(const pf_pool *pool, int T, int q_tokens, int32_
     if (pf_sel_count_impl(pool->policy_host[h], T) > pool->policy_host[h].slots) return PF_ERR_INVALID_ARG;
   const int variant = pf_resolve_variant(pool->head_dim);
   PfSegPlan plan;
-  if (getenv("PF_SEG_TILES")) {
+  if (pf_tuned_seg_tiles()) {
     memset(&plan, 0, sizeof(plan));
     plan.uniform = pf_resolve_seg_tiles(0);
   } else {

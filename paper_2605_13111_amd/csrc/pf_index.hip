@@ -218,7 +218,7 @@ extern "C" int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens
 
   const int variant = pf_resolve_variant(pool->head_dim);
   // segment lengths: the caller's, else the PF_SEG_TILES override, else planned for this launch
-  const bool fixed = index->seg_tiles > 0 || getenv("PF_SEG_TILES");
+  const bool fixed = index->seg_tiles > 0 || pf_tuned_seg_tiles() > 0;
   PfSegPlan plan;
   if (fixed) {
     memset(&plan, 0, sizeof(plan));
@@ -273,6 +273,11 @@ extern "C" int pf_build_index(const pf_pool *pool, pf_index *index, int q_tokens
     longest = 0;
     for (int h = 0; h < pool->n_heads; ++h) longest = pf_max(longest, plan.of(h));
   }
-  index->reserved = fixed ? 0 : longest;
+  index->longest_seg = fixed ? 0 : longest;
   return PF_OK;
+}
+
+extern "C" const int32_t *pf_index_status_dev(const pf_index *index) {
+  if (!index || !index->work) return nullptr;
+  return &((const PfWorkHeader *)index->work)->error;
 }

@@ -159,6 +159,7 @@ PF_HD size_t pf_partial_bytes(int bq, int head_dim) { return (size_t)bq * (head_
 int pf_validate_pool(const pf_pool *pool);                 // PF_OK or error
 bool pf_chunk_layout_ok(const pf_chunk_layout *lay, int n_heads, int tokens, int head_dim);   // null = packed = ok
 int pf_resolve_seg_tiles(int seg_tiles);                   // 0 -> default, else clamped to the minimum
+int pf_tuned_seg_tiles();                                  // the process-wide segment-length override, 0 = none
 int pf_resolve_variant(int head_dim);                      // kernel variant in use
 // Segment length that a host replay of the launch schedule finds best for this history length.
 void pf_auto_plan(const pf_pool *pool, int T, int q_tokens, int variant, bool queue, PfSegPlan *plan);

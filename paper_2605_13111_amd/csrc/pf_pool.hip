@@ -21,10 +21,8 @@ __global__ void pf_pool_reset_kernel(int32_t *n_frames, int32_t *frame_ids, floa
     frame_ids[i] = -1;
     frame_score[i] = 0.0f;
   }
-  if (i < n_heads) {
-    n_frames[i] = 0;
-    sync[i] = 0;
-  }
+  if (i < n_heads) n_frames[i] = 0;
+  if (i < (long long)n_heads * PF_SYNC_STRIDE) sync[i] = 0;
   if (i == 0) *T_dev = 0;
 }
 
@@ -193,11 +191,11 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
   // them) before it signals its arrival, and nobody reads the new tables or the payload before the kernel
   // ends, so the arrival needs no memory fence (a device-scope release here would write back the die's
   // whole L2 once per workgroup).  The arrival comes after the payload on purpose: atomics and loads return
-  // in order, and the counters of all heads share one cache line, so an early arrival would hold up the
-  // loads behind a queue of atomics (measured: 59 instead of 50 us). ----
+  // in order, so an early arrival would hold up the loads behind the atomics.  Every head's counter sits in a
+  // cache line of its own (PF_SYNC_STRIDE), so the arrivals of different heads do not queue behind each other. ----
   __syncthreads();
   if (tid == 0) {
-    const int arrived = atomicAdd(&P.sync[h], 1);
+    const int arrived = atomicAdd(&P.sync[h * PF_SYNC_STRIDE], 1);
     s_last = (arrived == 2 * P.blocks_per_head - 1) ? 1 : 0;
   }
   __syncthreads();
@@ -216,7 +214,7 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
   }
   if (tid == 0) {
     P.n_frames[h] = n_kept;
-    P.sync[h] = 0;
+    P.sync[h * PF_SYNC_STRIDE] = 0;
     if (h == 0) *P.T_dev = T_new;
   }
 }
@@ -274,7 +272,8 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_merge_kernel(PoolMergePa
 extern "C" int pf_pool_reset(pf_pool *pool, void *stream) {
   const int rc = pf_validate_pool(pool);
   if (rc != PF_OK) return rc;
-  const long long n = pool->total_slots > pool->n_heads ? pool->total_slots : pool->n_heads;
+  const long long n_sync = (long long)pool->n_heads * PF_SYNC_STRIDE;
+  const long long n = pool->total_slots > n_sync ? pool->total_slots : n_sync;
   const int threads = 256;
   const unsigned blocks = (unsigned)((n + threads - 1) / threads);
   hipLaunchKernelGGL(pf_pool_reset_kernel, dim3(blocks), dim3(threads), 0, (hipStream_t)stream, pool->n_frames,
@@ -299,6 +298,11 @@ static int cache_append_impl(pf_pool *pool, const void *k_new, const void *v_new
     if (pf_ret_count_impl(p, T_new) > p.slots - pf_veil_merged_slots(p)) return PF_ERR_CAPACITY;
     if (pf_ret_count_impl(p, pool->T_host) + n_new > POOL_MAX_CAND) return PF_ERR_CAPACITY;
   }
+  // heads with cache merging need a second launch; its grid is checked before the first one is enqueued, so a
+  // call that fails leaves host and device state as they were
+  int max_cap = 0;
+  for (int h = 0; h < pool->n_heads; ++h) max_cap = pf_max(max_cap, pf_veil_merged_slots(pool->policy_host[h]));
+  if ((long long)pool->n_heads * max_cap > 65535) return PF_ERR_UNSUPPORTED;
   PoolAppendParams P;
   P.k_pool = (uint4 *)pool->k_pool;
   P.v_pool = (uint4 *)pool->v_pool;
@@ -323,8 +327,6 @@ static int cache_append_impl(pf_pool *pool, const void *k_new, const void *v_new
                      (hipStream_t)stream, P);
   PF_HIP_CHECK(hipGetLastError());
   // heads with cache merging: a second launch rebuilds their merged frames from the frames just packed
-  int max_cap = 0;
-  for (int h = 0; h < pool->n_heads; ++h) max_cap = pf_max(max_cap, pf_veil_merged_slots(pool->policy_host[h]));
   if (max_cap > 0) {
     PoolMergeParams M;
     M.k_pool = (uint4 *)pool->k_pool;

@@ -63,12 +63,10 @@ def veil(sink, recent, slots=None):
     return HeadPolicy(VEIL, 0, sink, recent, 0, 1, slots if slots is not None else sink + recent)
 
 
-def veil_merged(sink, recent, n_merged, window, slots=None):
+def veil_merged(sink, recent, n_merged, window, slots):
     """Veil head with cache merging (Sec. 4.2): ``n_merged`` merged frames, each compressing a local window of
-    ``window`` frames.  Pool region: sink + recent + the window sources + the frames of one append, plus one slot
-    per merged frame at the end of the region."""
-    need = sink + recent + n_merged * window + 3 + n_merged
-    return HeadPolicy(VEIL, 0, sink, recent, n_merged, window, slots if slots is not None else need)
+    ``window`` frames.  ``slots`` = capacity of the head's pool region, chosen by the caller."""
+    return HeadPolicy(VEIL, 0, sink, recent, n_merged, window, slots)
 
 
 def drawn_policies(n_heads, seed, max_frames, topk_cap=18, veil_recent=3):
@@ -88,8 +86,9 @@ def drawn_policies(n_heads, seed, max_frames, topk_cap=18, veil_recent=3):
     return pols
 
 
-def policies(workload, layer=0, extra_frames=0):
-    """Policy table of one layer.  ``extra_frames`` adds pool capacity beyond the workload's history."""
+def policies(workload, layer=0, extra_frames=0, slots_of=None):
+    """Policy table of one layer.  ``extra_frames`` adds pool capacity beyond the workload's history.
+    ``slots_of``: see ``paper_default_policies`` (needed by ``c6_paper`` only)."""
     w = WORKLOADS[workload] if isinstance(workload, str) else workload
     cap_frames = w.history_frames + extra_frames
     if w.name == "c1_tiny":
@@ -101,15 +100,18 @@ def policies(workload, layer=0, extra_frames=0):
     if w.name in ("c3_step", "c5_stream"):
         return drawn_policies(w.n_heads, 7000 + layer, cap_frames)
     if w.name == "c6_paper":
-        return paper_default_policies(w.n_heads, 8000 + layer, cap_frames)
+        return paper_default_policies(w.n_heads, 8000 + layer, cap_frames, slots_of)
     if w.name == "c7_headwin":
         return head_window_policies(w.n_heads, 8000 + layer)
     raise KeyError(w.name)
 
 
-def paper_default_policies(n_heads, seed, max_frames, wave_period=6):
+def paper_default_policies(n_heads, seed, max_frames, slots_of, wave_period=6):
     """The paper's own hyper-parameters (experimental setup): sink 3, forced recent 4, capacities
-    Anchor/Wave/Veil 4/4/2, Veil merge window 2."""
+    Anchor/Wave/Veil 4/4/2, Veil merge window 2.  Capped Wave heads and Veil heads with merging retain a sliding
+    window of the history; how many pool slots that takes is the caller's to say: ``slots_of(policy) -> int`` is
+    applied to those heads (the tests size from the oracle's retained sets, the benchmark from the library's
+    closed-form count -- this module holds none of the method's arithmetic)."""
     g = _cpu_gen(seed)
     u = torch.rand(n_heads, generator=g)
     pols = []
@@ -117,9 +119,11 @@ def paper_default_policies(n_heads, seed, max_frames, wave_period=6):
         if u[h] < 0.4:
             pols.append(anchor_strided(4, max_frames, sink=3, recent=4))
         elif u[h] < 0.7:
-            pols.append(wave(wave_period, min(max_frames, 3 + 4 + 5 * wave_period), cap=4, sink=3, recent=4))
+            p = wave(wave_period, max_frames, cap=4, sink=3, recent=4)
+            pols.append(p._replace(slots=min(max_frames, slots_of(p))))
         else:
-            pols.append(veil_merged(3, 4, 2, 2))
+            p = veil_merged(3, 4, 2, 2, max_frames)
+            pols.append(p._replace(slots=slots_of(p)))
     return pols
 
 

@@ -5,6 +5,8 @@ import numpy as np
 
 from paper_2605_13111_amd import synth
 
+from oracle import policy as OP
+
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 _TYPE = {"A": synth.ANCHOR, "W": synth.WAVE, "V": synth.VEIL}
@@ -34,3 +36,20 @@ def dense_masked_attention(q, k_all, v_all, mask, scale):
     w = np.exp(logits)
     w = w / w.sum(axis=2, keepdims=True)
     return np.einsum("hij,hjd->hid", w, v_all), w
+
+
+def oracle_slots(max_T):
+    """slots_of callable for ``synth.paper_default_policies``: the most frames the oracle's retention rule ever
+    keeps for the head at history lengths 0 .. max_T, plus one slot per merged frame of a Veil head."""
+    def slots_of(pol):
+        big = pol._replace(slots=10 ** 6)
+        need = max(len(OP.retained_frames(big, T, range(T))) for T in range(max_T + 1))
+        return need + (pol.cap if pol.type == synth.VEIL and pol.cap > 0 else 0)
+    return slots_of
+
+
+def veil_merged(sink, recent, n_merged, window, slots=None, n_new=3):
+    """Veil head with cache merging whose pool region holds sink + recent + the window sources + the frames of one
+    append, plus one slot per merged frame at the end of the region."""
+    need = sink + recent + n_merged * window + n_new + n_merged
+    return synth.veil_merged(sink, recent, n_merged, window, slots if slots is not None else need)

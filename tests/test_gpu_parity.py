@@ -7,20 +7,19 @@ import torch
 
 from paper_2605_13111_amd import binding as B
 from paper_2605_13111_amd import synth
+import helpers
 import gpu_common as G
 
 pytestmark = pytest.mark.gpu
 
+DEFAULT_VARIANT = 1
+
 
 @pytest.fixture(params=[0, 1], ids=["w4x32", "pp8x32"])
 def variant(request):
-    old = os.environ.get("PF_ATTN_VARIANT")
-    os.environ["PF_ATTN_VARIANT"] = str(request.param)
+    B.pf_set_tuning(attn_variant=request.param)
     yield request.param
-    if old is None:
-        os.environ.pop("PF_ATTN_VARIANT", None)
-    else:
-        os.environ["PF_ATTN_VARIANT"] = old
+    B.pf_set_tuning(attn_variant=DEFAULT_VARIANT)
 
 
 def test_c1_tiny_full(variant):
@@ -184,7 +183,7 @@ def test_paper_default_policies_at_model_shape(variant):
     """The paper's own policy set (sink 3, recent 4, capacities 4/4/2: strided Anchor, capped Wave with its sliding
     retention window, Veil) after 14 three-frame chunks (42 history frames) at model shape: pool, index and
     cu_seqlens bit-exact, attention on sampled rows."""
-    pols = synth.paper_default_policies(12, 8003, 48)
+    pols = synth.paper_default_policies(12, 8003, 48, helpers.oracle_slots(48))
     rows = G.sample_rows(4680, 48, 31, extra=(1559, 1560, 3119, 3120))
     a, r = G.run_case(pols, 1560, 128, [3] * 14, 4680, seed=31, rows=rows, check_every_append=False, label="paper-default")
     print("paper-default policies: max-abs %.2e rel %.2e" % (a, r))
@@ -204,12 +203,12 @@ def test_veil_cache_merging(variant):
     """Veil heads with cache merging (Sec. 4.2) next to the other head types: merged frames bit-exact in the pool
     after every append (windows of 2 and of 3 frames, token counts that 3 does and does not divide), merged
     entries in the index, attention over [sink | merged | recent | chunk]."""
-    pols = [synth.veil_merged(3, 4, 2, 2), synth.veil_merged(1, 2, 1, 3), synth.veil_merged(1, 0, 3, 2), synth.veil(1, 3),
+    pols = [helpers.veil_merged(3, 4, 2, 2), helpers.veil_merged(1, 2, 1, 3), helpers.veil_merged(1, 0, 3, 2), synth.veil(1, 3),
             synth.anchor_all(24), synth.wave(3, 24)]
     a, r = G.run_case(pols, 200, 128, [3] * 7, 600, seed=41, label="veil-merging")
     a, r = G.run_case(pols[:4], 17, 64, [1] * 15, 40, seed=42, label="veil-merging-small")
     # the paper's defaults for Veil heads at model shape, sampled rows
-    pols = [synth.veil_merged(3, 4, 2, 2)] * 2 + synth.paper_default_policies(4, 8005, 40)
+    pols = [helpers.veil_merged(3, 4, 2, 2)] * 2 + synth.paper_default_policies(4, 8005, 40, helpers.oracle_slots(40))
     rows = G.sample_rows(4680, 32, 43, extra=(1559, 1560))
     G.run_case(pols, 1560, 128, [3] * 9, 4680, seed=43, rows=rows, check_every_append=False, label="veil-merging-model")
 
@@ -370,7 +369,7 @@ def test_whole_chunk_from_a_hip_graph():
         assert torch.equal(getattr(index_e, name), getattr(index_g, name)), name
 
 
-def test_work_queue_and_one_block_per_workgroup_agree(monkeypatch):
+def test_work_queue_and_one_block_per_workgroup_agree():
     """The pipelined kernel hands out its blocks through per-die queues (resident workgroups, stealing between
     dies).  With the segment length fixed, that launch and the plain one-block-per-workgroup launch compute the
     same blocks, so their outputs are equal bit for bit; so are repeated queue launches on one index (the tickets
@@ -392,11 +391,12 @@ def test_work_queue_and_one_block_per_workgroup_agree(monkeypatch):
     assert index.c.n_blocks > 1500
     outs = []
     for mode in ("1", "0", "1", "1"):
-        monkeypatch.setenv("PF_ATTN_QUEUE", mode)
+        B.pf_set_tuning(attn_queue=int(mode))
         o = torch.zeros((H, Lq, D), dtype=torch.bfloat16, device=dev)
         B.pf_ragged_attn_fwd(pool, index, q, kc, vc, o, ws)
         torch.cuda.synchronize()
         outs.append(o)
+    B.pf_set_tuning(attn_queue=1)
     for o in outs[1:]:
         assert torch.equal(outs[0].view(torch.int16), o.view(torch.int16))
     assert bool(torch.isfinite(outs[0].float()).all()) and float(outs[0].float().abs().max()) > 0

@@ -161,7 +161,7 @@ def _tiles(pol, T, tpf, q_tokens):
     return -(-(B.pf_selected_count(pol, T) * tpf + q_tokens) // 64)
 
 
-def test_launch_plan_stays_inside_the_advertised_buffers(monkeypatch):
+def test_launch_plan_stays_inside_the_advertised_buffers():
     """pf_plan_segments (host only) returns the plan pf_build_index would launch.  For the bench workload's drawn
     policies at several history lengths, in both launch forms and with the per-head step switched off: every split
     head's segments are at least 48 tiles long, the block and partial counts follow from the segment lengths, and
@@ -174,11 +174,9 @@ def test_launch_plan_stays_inside_the_advertised_buffers(monkeypatch):
         pool = _fake_pool(pols, tpf=tpf, D=D)
         work_bytes = B.lib().pf_index_work_bytes(ctypes.byref(pool), Lq)
         ws_bytes = B.lib().pf_attn_workspace_bytes(ctypes.byref(pool), Lq)
-        for env in ({}, {"PF_ATTN_QUEUE": "0"}, {"PF_PLAN_UNIFORM": "1"}):
-            for k in ("PF_ATTN_QUEUE", "PF_PLAN_UNIFORM"):
-                monkeypatch.delenv(k, raising=False)
-            for k, v in env.items():
-                monkeypatch.setenv(k, v)
+        for env in ({}, {"attn_queue": 0}, {"plan_uniform": 1}):
+            B.pf_set_tuning(attn_variant=1, attn_queue=1, seg_tiles=0, plan_uniform=0)
+            B.pf_set_tuning(**env)
             for T in (0, 3, 21, 57):
                 seg, n_blocks, n_partials = B.pf_plan_segments(pool, T, Lq)
                 assert B.pf_plan_segments(pool, T, Lq) == (seg, n_blocks, n_partials)       # remembered, same answer
@@ -192,8 +190,47 @@ def test_launch_plan_stays_inside_the_advertised_buffers(monkeypatch):
                 assert n_blocks == -(-teams // 8) * 8 * n_qt and n_partials == parts
                 assert n_partials * 256 * (D + 2) * 4 <= ws_bytes
                 assert 64 + 4 * (len(pols) * n_qt + 16) + 16 * len(pols) + 32 * n_blocks <= work_bytes
-                if env.get("PF_PLAN_UNIFORM"):
+                if env.get("plan_uniform"):
                     assert len(set(seg)) == 1
+    B.pf_set_tuning(attn_variant=1, attn_queue=1, seg_tiles=0, plan_uniform=0)
+
+
+def test_tuning_switches_validate_and_apply():
+    assert B.lib().pf_set_tuning(7, -1, -1, -1) == B.PF_ERR_INVALID_ARG
+    pool = _fake_pool(synth.policies("c3_step", layer=0), tpf=1560, D=128)
+    B.pf_set_tuning(seg_tiles=64)
+    seg, _, _ = B.pf_plan_segments(pool, 57, 4680)
+    assert set(seg) == {64}
+    B.pf_set_tuning(seg_tiles=0)
+    seg, _, _ = B.pf_plan_segments(pool, 57, 4680)
+    assert min(seg) >= 48
+
+
+def test_planning_a_streaming_rollout_is_cheap_once_seen():
+    """The one-frame-chunk rollout asks for 30 layers x 40 history lengths = 1200 different launch plans.  The
+    library remembers all of them: a second rollout pays a table lookup per call (budget: 50 us mean, measured
+    ~3 us), and a first-time plan stays in the low milliseconds."""
+    import time
+    w = synth.WORKLOADS["c5_stream"]
+    pools = [_fake_pool(synth.policies("c5_stream", layer=l), tpf=w.tokens_per_frame, D=w.head_dim) for l in range(w.n_layers)]
+    B.pf_set_tuning(attn_variant=1, attn_queue=1, seg_tiles=0, plan_uniform=0)
+
+    def rollout():
+        plans, worst = [], 0.0
+        t0 = time.perf_counter()
+        for T in range(w.history_frames):
+            for pool in pools:
+                t1 = time.perf_counter()
+                plans.append(B.pf_plan_segments(pool, T, w.tokens_per_frame))
+                worst = max(worst, time.perf_counter() - t1)
+        return plans, (time.perf_counter() - t0) / len(plans), worst
+
+    first, mean1, worst1 = rollout()
+    again, mean2, worst2 = rollout()
+    assert first == again
+    print("plan per call: first rollout %.1f us mean / %.2f ms worst, second %.1f us mean" % (mean1 * 1e6, worst1 * 1e3, mean2 * 1e6))
+    assert mean2 <= 50e-6
+    assert mean1 <= 2e-3
 
 
 def test_launch_plan_rejects_bad_arguments():

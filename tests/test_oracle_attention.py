@@ -10,6 +10,7 @@ from oracle import attention as A
 from oracle import policy as P
 from oracle.pool import PoolOracle
 from paper_2605_13111_amd import synth
+import helpers
 from helpers import dense_masked_attention
 
 
@@ -174,7 +175,7 @@ def test_veil_cache_merging_equals_a_token_level_mask(m, tpf):
     EVERY raw token with the mask 'token tok of frame w0+i is visible iff tok mod m == i' written down here."""
     H, D, T, Lq = 2, 64, 17, 5
     S, R, cap = 2, 3, 2
-    pols = [synth.veil_merged(S, R, cap, m), synth.veil_merged(1, 0, 1, m)]
+    pols = [helpers.veil_merged(S, R, cap, m), helpers.veil_merged(1, 0, 1, m)]
     k_hist = synth.randn_bf16((H, T, tpf, D), 71)
     v_hist = synth.randn_bf16((H, T, tpf, D), 72)
     q = synth.randn_bf16((H, Lq, D), 73)

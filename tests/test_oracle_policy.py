@@ -8,6 +8,7 @@ import pytest
 
 from oracle import policy as P
 from paper_2605_13111_amd import synth
+import helpers
 from helpers import read_policy_fixture
 
 
@@ -135,6 +136,46 @@ def test_selection_is_always_retained_when_streaming():
                 assert resident == P.retained_frames(pol, T, list(range(T)), score)
 
 
+def test_hand_worked_retained_sets():
+    """tests/golden/retained_cases.txt: the exact retained set, worked out by hand from Eq. 5 / Observation 1."""
+    n = 0
+    for pol, T, expect, source in read_policy_fixture("retained_cases.txt"):
+        want = [int(x) for x in expect.split()]
+        assert P.retained_frames(pol, T, range(T)) == want, (pol, T, source)
+        n += 1
+    assert n >= 6
+
+
+def test_retention_keeps_exactly_what_a_later_step_can_select():
+    """For the policies that evict (capped Wave, Veil with and without merging, Anchor top-k with static scores) the
+    retained set at history length T equals the union, over this and every later step, of the history frames below
+    T that the step attends to: nothing is missing (sufficiency) and nothing is kept in vain (no over-retention)."""
+    rng = np.random.default_rng(11)
+    score = {f: np.float32(rng.integers(0, 40)) / np.float32(3) for f in range(400)}
+    pols = []
+    for S in (0, 1, 3):
+        for R in (0, 2, 4):
+            pols.append(synth.HeadPolicy(synth.VEIL, 0, S, R, 0, 1, 10 ** 6))
+            for cap in (1, 2, 4):
+                for period in (1, 2, 3, 6):
+                    pols.append(synth.HeadPolicy(synth.WAVE, 0, S, R, cap, period, 10 ** 6))
+                    pols.append(synth.HeadPolicy(synth.VEIL, 0, S, R, cap, period, 10 ** 6))
+                pols.append(synth.HeadPolicy(synth.ANCHOR, synth.MODE_TOPK, S, R, cap, 1, 10 ** 6))
+    M = P.MERGED
+    for pol in pols:
+        horizon = pol.recent + (pol.cap + 1) * max(pol.period, 1) + pol.sink + 2     # later steps that can still reach below T
+        for T in (0, 1, 5, 13, 30):
+            needed = set()
+            for T2 in range(T, T + horizon + 1):
+                for f in P.selected_frames(pol, T2, {g: score[g] for g in range(T2)}):
+                    if f & M:                                  # a merged window needs its m source frames
+                        needed |= {g for g in range(f & ~M, (f & ~M) + pol.period) if g < T}
+                    elif f < T:
+                        needed.add(f)
+            kept = P.retained_frames(pol, T, range(T), {g: score[g] for g in range(T)})
+            assert set(kept) == needed, (pol, T, sorted(needed), kept)
+
+
 def test_cu_seqlens_is_an_exclusive_prefix_sum():
     """Sec. 4.3: cu_seqlens_i = sum of the lengths before sequence i; sequence i occupies [cu_i, cu_{i+1})."""
     assert P.cu_seqlens([12, 4, 3, 3], 16) == [0, 192, 256, 304, 352]
@@ -150,7 +191,7 @@ def test_cu_seqlens_is_an_exclusive_prefix_sum():
 def test_veil_merging_windows_and_key_sequence():
     """Paper defaults for Veil heads: sink 3, forced recent 4, 2 merged frames, window 2.  At T = 20 the recent
     frames are 16..19, so the windows are [14,16) and [12,14); each is ONE entry of the key sequence."""
-    pol = synth.veil_merged(3, 4, 2, 2)
+    pol = helpers.veil_merged(3, 4, 2, 2)
     M = P.MERGED
     assert P.selected_frames(pol, 20) == [0, 1, 2, M | 12, M | 14, 16, 17, 18, 19]
     # a window exists only if it lies entirely between the sink and the recent frames
@@ -159,7 +200,7 @@ def test_veil_merging_windows_and_key_sequence():
     assert P.selected_frames(pol, 5) == [0, 1, 2, 3, 4]                         # sink and recent overlap
     assert P.selected_frames(pol, 0) == []
     # without forced recent frames the window is the m frames before the current one: merged(t-m : t)
-    assert P.selected_frames(synth.veil_merged(1, 0, 1, 3), 10) == [0, M | 7]
+    assert P.selected_frames(helpers.veil_merged(1, 0, 1, 3), 10) == [0, M | 7]
     # retention: sink, recent, and the Cap*m frames the windows of this and any later step are made of
     assert P.retained_frames(pol, 20, range(20)) == [0, 1, 2] + list(range(12, 20))
     # cap = 0 is the plain Veil policy

@@ -5,6 +5,7 @@ import pytest
 from oracle import policy as P
 from oracle.pool import PoolOracle, CapacityError
 from paper_2605_13111_amd import synth
+import helpers
 
 
 def _frames(H, n, tpf, D, first_id):
@@ -22,7 +23,7 @@ def test_veil_merging_pool_layout_and_streaming():
     """Merged frames sit in the last slots of the head's region (window j, 0 = nearest, in slot slots-1-j), are
     rebuilt from the raw frames at every history length, and the raw frames a later window needs stay resident."""
     tpf, D = 6, 8
-    pol = synth.veil_merged(2, 3, 2, 2)
+    pol = helpers.veil_merged(2, 3, 2, 2)
     pool = PoolOracle([pol], tpf, D)
     k, v = _frames(1, 30, tpf, D, 0)
     for t in range(30):
@@ -42,7 +43,7 @@ def test_veil_merging_pool_layout_and_streaming():
             else:
                 assert ids[slot] == -1
     # streaming == batch: one append of everything gives the same state
-    batch = PoolOracle([synth.veil_merged(2, 3, 2, 2, slots=40)], tpf, D)
+    batch = PoolOracle([helpers.veil_merged(2, 3, 2, 2, slots=40)], tpf, D)
     batch.append(k, v)
     assert [f[0] for f in batch.frames[0]] == [f[0] for f in pool.frames[0]]
     assert batch.merged_windows(0)[0][1] == pool.merged_windows(0)[0][1]
