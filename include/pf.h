@@ -276,6 +276,22 @@ int pf_ragged_attn_fwd_strided(const pf_pool *pool, const pf_index *index,
                                void *workspace, size_t workspace_bytes,
                                const pf_chunk_layout *layout, void *stream);
 
+/*
+ * pf_ragged_attn_fwd for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  The partial results of split heads go to a fixed
+ * 160 MiB array inside the library's device image instead of `workspace` (each GPU the library runs on holds its
+ * own copy until the process ends); everything else -- arguments, result, errors -- is as for pf_ragged_attn_fwd
+ * with packed chunk tensors.  PF_ERR_CAPACITY when the launch plan of `index` needs more than 160 MiB of partial
+ * results (n_partials x 256 rows x (head_dim + 2) floats; the 30-layer configuration's layers need up to 133 MiB).
+ * The call allocates nothing and frees nothing; the array's address on the current device is looked up at the
+ * first call on that device (so make one call per device before capturing a graph).  All calls on one GPU share
+ * the array: launches that use it must not overlap in time (same stream, or ordered by events), whatever pool or
+ * index they belong to.  Nothing in it needs clearing: every partial is written in full before it is read.
+ */
+int pf_ragged_attn_fwd_static(const pf_pool *pool, const pf_index *index,
+                              const void *q, const void *k_cur, const void *v_cur, void *out,
+                              int q_tokens, float softmax_scale, void *stream);
+
 /* ---- before the hot path: which head gets which policy -------------------- */
 
 /*

@@ -17,7 +17,7 @@ PF_SYNC_STRIDE = 32            # int32 words between the per-head counters of pf
 
 EXPORTS = ["pf_index_work_bytes", "pf_attn_workspace_bytes", "pf_selected_count", "pf_retained_count", "pf_plan_segments",
            "pf_pool_reset", "pf_cache_append", "pf_cache_append_strided", "pf_build_index", "pf_ragged_attn_fwd",
-           "pf_ragged_attn_fwd_strided", "pf_classify_heads", "pf_status_string", "pf_set_tuning", "pf_index_status_dev"]
+           "pf_ragged_attn_fwd_strided", "pf_classify_heads", "pf_status_string", "pf_set_tuning", "pf_index_status_dev", "pf_ragged_attn_fwd_static"]
 
 
 class pf_head_policy(ctypes.Structure):
@@ -81,6 +81,8 @@ def lib():
         L.pf_ragged_attn_fwd_strided.restype = I
         L.pf_ragged_attn_fwd_strided.argtypes = [P(pf_pool), P(pf_index), V, V, V, V, I, ctypes.c_float, V, ctypes.c_size_t,
                                                  P(pf_chunk_layout), V]
+        L.pf_ragged_attn_fwd_static.restype = I
+        L.pf_ragged_attn_fwd_static.argtypes = [P(pf_pool), P(pf_index), V, V, V, V, I, ctypes.c_float, V]
         L.pf_classify_heads.restype = I
         L.pf_classify_heads.argtypes = [V, I, I, I, ctypes.c_double, ctypes.c_double, V, V, V, V]
         L.pf_set_tuning.restype = I
@@ -269,6 +271,16 @@ def pf_ragged_attn_fwd(pool, index, q, k_cur, v_cur, out, workspace, softmax_sca
     _check(lib().pf_ragged_attn_fwd(ctypes.byref(pool.c), ctypes.byref(index.c), _ptr(q), _ptr(k_cur), _ptr(v_cur),
                                     _ptr(out), int(q.shape[1]), float(softmax_scale), _ptr(workspace), ws_bytes,
                                     _stream(stream)), "pf_ragged_attn_fwd")
+
+
+def pf_ragged_attn_fwd_static(pool, index, q, k_cur, v_cur, out, softmax_scale=0.0, stream=None):
+    """pf_ragged_attn_fwd without a workspace argument: partial results go to the library's own fixed device array."""
+    for t in (q, k_cur, v_cur, out):
+        assert t.is_contiguous() and t.dtype == torch.bfloat16 and tuple(t.shape) == tuple(q.shape)
+    assert q.shape[0] == pool.n_heads and q.shape[2] == pool.D
+    _check(lib().pf_ragged_attn_fwd_static(ctypes.byref(pool.c), ctypes.byref(index.c), _ptr(q), _ptr(k_cur), _ptr(v_cur),
+                                           _ptr(out), int(q.shape[1]), float(softmax_scale), _stream(stream)),
+           "pf_ragged_attn_fwd_static")
 
 
 def pf_ragged_attn_fwd_strided(pool, index, q, k_cur, v_cur, out, workspace, softmax_scale=0.0, stream=None):

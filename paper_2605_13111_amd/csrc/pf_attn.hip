@@ -20,6 +20,7 @@
 #include <stddef.h>
 #include <stdlib.h>
 #include "pf_internal.h"
+#include <mutex>
 #include <utility>
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -1129,6 +1130,42 @@ extern "C" int pf_ragged_attn_fwd(const pf_pool *pool, const pf_index *index, co
                                   const void *v_cur, void *out, int q_tokens, float softmax_scale,
                                   void *workspace, size_t workspace_bytes, void *stream) {
   return attn_fwd_impl(pool, index, q, k_cur, v_cur, out, q_tokens, softmax_scale, workspace, workspace_bytes, nullptr, stream);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// The same launch for callers that cannot allocate device memory or bring a workspace (code under graph capture,
+// tight serving loops): the partial results of split heads go to a fixed array in the library's own device image.
+// Every GPU holds its own copy of the array at its own address, looked up once per device.
+// ---------------------------------------------------------------------------------------------------
+constexpr size_t PF_STATIC_SCRATCH_BYTES = 160ull << 20;
+static __device__ __align__(256) unsigned char scratch[PF_STATIC_SCRATCH_BYTES];
+
+static int static_scratch_ptr(void **out) {
+  static std::mutex mu;
+  static void *ptr_of[64] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return PF_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PF_ERR_HIP;
+    ptr_of[dev] = p;
+  }
+  *out = ptr_of[dev];
+  return PF_OK;
+}
+
+extern "C" int pf_ragged_attn_fwd_static(const pf_pool *pool, const pf_index *index, const void *q, const void *k_cur,
+                                         const void *v_cur, void *out, int q_tokens, float softmax_scale, void *stream) {
+  if (!pool || !index) return PF_ERR_INVALID_ARG;
+  if (index->variant < 0 || index->variant >= PF_NUM_VARIANTS || index->n_partials < 0) return PF_ERR_INVALID_ARG;
+  if (pool->head_dim != 64 && pool->head_dim != 128) return PF_ERR_UNSUPPORTED;
+  const size_t need = (size_t)index->n_partials * pf_partial_bytes(pf_variant_bq(index->variant), pool->head_dim);
+  if (need > PF_STATIC_SCRATCH_BYTES) return PF_ERR_CAPACITY;
+  void *ws = nullptr;
+  const int rc = static_scratch_ptr(&ws);
+  if (rc != PF_OK) return rc;
+  return attn_fwd_impl(pool, index, q, k_cur, v_cur, out, q_tokens, softmax_scale, ws, PF_STATIC_SCRATCH_BYTES, nullptr, stream);
 }
 
 extern "C" int pf_ragged_attn_fwd_strided(const pf_pool *pool, const pf_index *index, const void *q, const void *k_cur,

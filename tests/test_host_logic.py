@@ -121,6 +121,23 @@ def test_argument_validation_without_a_device():
     assert B.lib().pf_status_string(B.PF_ERR_CAPACITY) == b"capacity exceeded"
 
 
+def test_static_scratch_entry_point_rejects_plans_that_do_not_fit():
+    """pf_ragged_attn_fwd_static keeps partial results in a fixed 160 MiB array: a plan that needs more is refused
+    on the host with a capacity error, before anything touches a device."""
+    lib = B.lib()
+    pool = _fake_pool([synth.anchor_all(4), synth.veil(1, 2)], tpf=1560, D=128)
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    slot = 256 * (128 + 2) * 4
+    too_many = (160 << 20) // slot + 1
+    idx = B.pf_index(8, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 20, 48, 0, 8, too_many, 1, 0)
+    assert lib.pf_ragged_attn_fwd_static(ctypes.byref(pool), ctypes.byref(idx), fake, fake, fake, fake, 48, 0.0,
+                                         null) == B.PF_ERR_CAPACITY
+    assert lib.pf_ragged_attn_fwd_static(None, ctypes.byref(idx), fake, fake, fake, fake, 48, 0.0, null) == B.PF_ERR_INVALID_ARG
+    idx.n_partials = -1
+    assert lib.pf_ragged_attn_fwd_static(ctypes.byref(pool), ctypes.byref(idx), fake, fake, fake, fake, 48, 0.0,
+                                         null) == B.PF_ERR_INVALID_ARG
+
+
 def test_chunk_layout_validation_without_a_device():
     """Strided entry points: stride checks happen on the host, before any device access."""
     lib = B.lib()
