@@ -172,7 +172,12 @@ __device__ __forceinline__ void attn_store_rows(const u32x4 (&reg)[NP], __bf16 *
 struct TileSrc {
   bool simple;            // tile inside one frame (or the chunk) and not ragged: base + row * stride
   bool strided;           // simple chunk tile whose rows are cur_stride elements apart instead of D
-  const __bf16 *kb, *vb;  // first row of the tile (simple case)
+  bool split;             // whole tile made of two dense runs: rows below n1 end one frame, the others start the next
+                          // frame (or the packed chunk); never together with simple
+  const __bf16 *kb, *vb;  // first row of the tile (simple case); of the first run (split case)
+  const __bf16 *kb2, *vb2; // split case: where row 0 of the tile WOULD sit if the second run began there (second run's
+                          // first row minus n1 rows), so that both runs are addressed by the row number in the tile
+  int n1;                 // split case: rows of the first run, 1 .. 63
   int kt;
 };
 __device__ __forceinline__ TileSrc tile_src(int kt, TilePos pos, const HeadKV &H, int D) {
@@ -182,10 +187,24 @@ __device__ __forceinline__ TileSrc tile_src(int kt, TilePos pos, const HeadKV &H
   t.simple = last >= PF_BK - 1 && (!in_hist || pos.r + PF_BK <= H.tpf);
   t.strided = !in_hist && H.cur_stride != D;
   t.kt = kt;
+  // a whole history tile that crosses exactly one border: frames of at least a tile, and the next run (a frame, or the
+  // chunk with rows D apart) holds the rest of the tile
+  t.n1 = H.tpf - pos.r;
+  t.split = !t.simple && in_hist && last >= PF_BK - 1 && H.tpf >= PF_BK && t.n1 > 0 && t.n1 < PF_BK &&
+            (pos.j + 1 < H.n_sel || H.cur_stride == D);
   size_t e = 0;
   if (t.simple) e = in_hist ? ((size_t)H.slots[pos.j] * H.tpf + pos.r) * D : (size_t)pos.r * H.cur_stride;
+  if (t.split) e = ((size_t)H.slots[pos.j] * H.tpf + pos.r) * D;
   t.kb = (in_hist ? H.k_pool : H.k_cur) + e;
   t.vb = (in_hist ? H.v_pool : H.v_cur) + e;
+  t.kb2 = t.kb;
+  t.vb2 = t.vb;
+  if (t.split) {
+    const bool next_hist = pos.j + 1 < H.n_sel;
+    const long long e2 = (next_hist ? (long long)H.slots[pos.j + 1] * H.tpf * D : 0ll) - (long long)t.n1 * D;
+    t.kb2 = (next_hist ? H.k_pool : H.k_cur) + e2;
+    t.vb2 = (next_hist ? H.v_pool : H.v_cur) + e2;
+  }
   return t;
 }
 // V^T operand of O^T += V^T P^T for 16 keys x 32 channels: two LDS transpose reads whose row choice
@@ -778,20 +797,21 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   // vector offset that never changes, and the second group is the instruction's immediate offset (it moves the
   // LDS destination along with the source).  Next to MFMAs this form costs almost nothing, whereas a global
   // load with a 64-bit address per lane held up the SIMD for ~65 cycles per instruction (measured).
-  auto copy_group = [&](const TileSrc &src, int snk, int snv, int h) {
+  auto copy_group_at = [&](const __bf16 *kbase, const __bf16 *vbase, int snk, int snv, int h) {
     constexpr unsigned RSRC_FLAGS = 0x00020000u;               // raw buffer, 32-bit data format
     if (h < 2) {
-      const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)src.kb, 0, PP_TILE_BYTES, RSRC_FLAGS);
+      const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)kbase, 0, PP_TILE_BYTES, RSRC_FLAGS);
       lptr_t dst = (lptr_t)(&sK[snk][wrow_bytes]);
       if (h == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofK0, wrow_bytes, 0, 0);
       else __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofK1, wrow_bytes, 1024, 0);
     } else {
-      const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)src.vb, 0, PP_TILE_BYTES, RSRC_FLAGS);
+      const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)vbase, 0, PP_TILE_BYTES, RSRC_FLAGS);
       lptr_t dst = (lptr_t)(&sV[snv][wrow_bytes]);
       if (h == 2) __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofV, wrow_bytes, 0, 0);
       else __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofV, wrow_bytes, 1024, 0);
     }
   };
+  auto copy_group = [&](const TileSrc &src, int snk, int snv, int h) { copy_group_at(src.kb, src.vb, snk, snv, h); };
   // The same for a chunk tile whose token rows are cur_stride elements apart (the model's [tokens][heads][D]
   // layout): the lane's row is part of its vector offset, the wave's first row and the second group are scalar
   // offsets, and the second group's LDS destination moves by hand.
@@ -805,7 +825,34 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     lptr_t dst = h < 2 ? (lptr_t)(&sK[snk][wrow_bytes + (h & 1) * 1024]) : (lptr_t)(&sV[snv][wrow_bytes + (h & 1) * 1024]);
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, h == 0 ? sofK0 : h == 1 ? sofK1 : sofV, soff, 0, 0);
   };
-  // whole tile at once (prologue, and tiles that cross a frame border or hold the ragged end)
+  // A tile made of two dense runs (it crosses a frame border): a 4-row group lies in the first run, in the second, or
+  // (when the border is not a multiple of 4 rows into the tile) in both, and then each run's lanes copy under their
+  // own execution mask: the LDS address of such a copy follows the lane number, so masked-off lanes leave their
+  // 16 bytes to the other instruction.  Returns the number of copy instructions issued.
+  auto copy_tile_split = [&](const TileSrc &src, int snk, int snv) __attribute__((always_inline)) -> int {
+    int n = 0;
+    const __bf16 *ka = src.kb, *va = src.vb, *kb2 = src.kb2, *vb2 = src.vb2;
+    const int n1 = src.n1;
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const int row0 = wave * 8 + (h & 1) * 4;
+      if (row0 + 4 <= n1) {
+        copy_group_at(ka, va, snk, snv, h);
+        n += 1;
+      } else if (row0 >= n1) {
+        copy_group_at(kb2, vb2, snk, snv, h);
+        n += 1;
+      } else {
+        int lane_l = lane;
+        asm volatile("" : "+v"(lane_l));                        // rare: its lane test is not held in a register through the loop
+        if (row0 + (lane_l >> 4) < n1) copy_group_at(ka, va, snk, snv, h);
+        else copy_group_at(kb2, vb2, snk, snv, h);
+        n += 2;
+      }
+    }
+    return n;
+  };
+  // whole tile at once (prologue; tiles that cross a frame border or hold the ragged end go row by row here)
   auto copy_tile_now = [&](int kt, const TilePos &tp, int snk, int snv) -> int {
     const TileSrc src = tile_src(kt, tp, H, D);
     if (src.simple) {
@@ -883,8 +930,9 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   // ---- plan of the next copy (made in one vector phase and carried out at the start of the next, so the
   // scalar load of a frame's slot has a whole tile time to arrive) ----
   TileSrc nsrc;
-  nsrc.kb = nsrc.vb = nullptr;
-  nsrc.simple = false;
+  nsrc.kb = nsrc.vb = nsrc.kb2 = nsrc.vb2 = nullptr;
+  nsrc.simple = nsrc.split = false;
+  nsrc.n1 = 0;
   int ncopy_kt = -1;                                           // tile planned for the next copy, -1: none
   int run_left = 0;                                            // tiles after the planned one that continue its source run
   long long run_step = 0;                                      // elements from one tile of the run to the next
@@ -961,6 +1009,8 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
 #pragma unroll
         for (int h = 0; h < 4; ++h) copy_group_strided(nsrc, snk, snv, h);
         n_last = 4;
+      } else if (nsrc.split) {
+        n_last = copy_tile_split(nsrc, snk, snv);
       } else {
         pp_copy_rows_slow<false>(ncopy_kt, H, sK[snk], wave, lane);
         pp_copy_rows_slow<true>(ncopy_kt, H, sV[snv], wave, lane);

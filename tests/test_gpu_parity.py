@@ -43,6 +43,15 @@ def test_mixed_policies_ragged_tails_full(variant, D):
     print("mixed D=%d max-abs %.2e rel %.2e" % (D, a, r))
 
 
+@pytest.mark.parametrize("tpf", [90, 65, 127])
+def test_tiles_crossing_frame_borders_at_odd_rows(variant, tpf):
+    """Frames of at least one tile whose length is no multiple of 4: a 64-key tile crosses a frame border (or the border
+    between the last selected frame and the chunk) at rows that split a wave's 4-row copy groups.  Full comparison."""
+    pols = [synth.anchor_all(14), synth.wave(2, 14), synth.veil(2, 3), synth.anchor_topk(5, 5)]
+    a, r = G.run_case(pols, tpf, 128, [3, 3, 3, 3], 2 * tpf + 7, seed=300 + tpf, label="odd-borders")
+    print("tpf %d max-abs %.2e rel %.2e" % (tpf, a, r))
+
+
 def test_peaked_logits(variant):
     """Queries x8: softmax close to one-hot, exercises the running-max rescaling."""
     a, r = G.run_case(_mixed(12), 48, 128, [3, 3, 3, 3], 200, seed=5, q_gain=8.0, seg_tiles=16, label="peaked")
