@@ -8,11 +8,13 @@
 // order: no synchronisation between workgroups is needed and the copy streams at HBM speed.
 #include "pf_internal.h"
 
+typedef __attribute__((ext_vector_type(4))) unsigned int pool_unit;   // one 16-byte unit of payload (a native vector: arrays of it stay in registers)
 constexpr int POOL_THREADS = 256;
 constexpr int POOL_UNITS_PER_THREAD = 2;                    // 16-byte units per thread per frame
 constexpr int POOL_CHUNK_UNITS = POOL_THREADS * POOL_UNITS_PER_THREAD;
 constexpr int POOL_MAX_CAND = 1024;                         // resident + new frames of one head (20 KB of tables per workgroup)
 constexpr int POOL_MOVE_BATCH = 8;                          // frames in flight per thread
+constexpr int POOL_PREFETCH = 4;                            // new frames whose payload is requested before the plan is made
 
 __global__ void pf_pool_reset_kernel(int32_t *n_frames, int32_t *frame_ids, float *frame_score,
                                      int32_t *T_dev, int32_t *sync, int n_heads, long long total_slots) {
@@ -50,7 +52,9 @@ __device__ __forceinline__ bool middle_kept(const pf_head_policy &p, int T, int 
   return p.cap > 0 && f >= T - p.recent - p.cap * p.period;
 }
 
-__global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppendParams P) {
+// Four or five workgroups share a compute unit, so a wave may take up to 128 registers: the batch of loads and the
+// prefetched new frames stay in flight together instead of being parked (and waited for) early.
+__global__ __launch_bounds__(POOL_THREADS) __attribute__((amdgpu_waves_per_eu(1, 4))) void pf_pool_append_kernel(PoolAppendParams P) {
   __shared__ int32_t s_id[POOL_MAX_CAND];
   __shared__ float s_score[POOL_MAX_CAND];
   __shared__ int32_t s_dest[POOL_MAX_CAND];     // destination slot or -1 (evicted)
@@ -68,6 +72,34 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
   const int n_old = P.n_frames[h];
   const int n_cand = n_old + P.n_new;
   const int T_new = P.T + P.n_new;
+
+  // ---- the new frames' payload does not depend on the plan (only its destination does): this thread's share of the
+  // first POOL_PREFETCH new frames is requested before the tables are even read, so these loads travel while the
+  // plan below is worked out ----
+  const pool_unit *fresh = (const pool_unit *)(is_v ? P.v_new : P.k_new) + (size_t)h * P.new_head_units;
+  const long long new_frame_units = (long long)(P.frame_units >> P.row_shift) * P.new_tok_units;   // tokens per frame x token stride
+  const int u0 = blockIdx.x * POOL_CHUNK_UNITS + tid;
+  bool valid[POOL_UNITS_PER_THREAD];
+  int unit_c[POOL_UNITS_PER_THREAD];
+  long long fresh_off[POOL_UNITS_PER_THREAD];
+#pragma unroll
+  for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u) {
+    const int unit = u0 + u * POOL_THREADS;
+    valid[u] = unit < P.frame_units;
+    unit_c[u] = valid[u] ? unit : 0;
+    // a new frame's token rows may be strided: unit -> (token, 16-byte piece of its row)
+    fresh_off[u] = (long long)(unit_c[u] >> P.row_shift) * P.new_tok_units + (unit_c[u] & ((1 << P.row_shift) - 1));
+  }
+  static_assert(POOL_PREFETCH == 4 && POOL_UNITS_PER_THREAD == 2, "the prefetched frames are held in named registers");
+  pool_unit nf00, nf01, nf10, nf11, nf20, nf21, nf30, nf31;
+  {
+    const pool_unit *f0 = fresh, *f1 = fresh + (size_t)pf_min(1, P.n_new - 1) * new_frame_units;
+    const pool_unit *f2 = fresh + (size_t)pf_min(2, P.n_new - 1) * new_frame_units, *f3 = fresh + (size_t)pf_min(3, P.n_new - 1) * new_frame_units;
+    nf00 = f0[fresh_off[0]]; nf01 = f0[fresh_off[1]];
+    nf10 = f1[fresh_off[0]]; nf11 = f1[fresh_off[1]];
+    nf20 = f2[fresh_off[0]]; nf21 = f2[fresh_off[1]];
+    nf30 = f3[fresh_off[0]]; nf31 = f3[fresh_off[1]];
+  }
 
   for (int j = tid; j < n_cand; j += POOL_THREADS) {
     if (j < n_old) {
@@ -150,40 +182,47 @@ __global__ __launch_bounds__(POOL_THREADS) void pf_pool_append_kernel(PoolAppend
   // ---- payload: this workgroup owns 16-byte units [u0, u0+POOL_CHUNK_UNITS) of every frame.  The loads of a
   // batch are unconditional (indices clamped, the source chosen by a select) so that all of them are in flight
   // before the first store; only the stores are predicated. ----
-  uint4 *pool = (is_v ? P.v_pool : P.k_pool) + (size_t)base * P.frame_units;
-  const uint4 *fresh = (is_v ? P.v_new : P.k_new) + (size_t)h * P.new_head_units;
-  const long long new_frame_units = (long long)(P.frame_units >> P.row_shift) * P.new_tok_units;   // tokens per frame x token stride
-  const int u0 = blockIdx.x * POOL_CHUNK_UNITS + tid;
-  bool valid[POOL_UNITS_PER_THREAD];
-  int unit_c[POOL_UNITS_PER_THREAD];
-  long long fresh_off[POOL_UNITS_PER_THREAD];
-#pragma unroll
-  for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u) {
-    const int unit = u0 + u * POOL_THREADS;
-    valid[u] = unit < P.frame_units;
-    unit_c[u] = valid[u] ? unit : 0;
-    // a new frame's token rows may be strided: unit -> (token, 16-byte piece of its row)
-    fresh_off[u] = (long long)(unit_c[u] >> P.row_shift) * P.new_tok_units + (unit_c[u] & ((1 << P.row_shift) - 1));
-  }
-  for (int m0 = 0; m0 < n_moves; m0 += POOL_MOVE_BATCH) {
-    uint4 r[POOL_MOVE_BATCH][POOL_UNITS_PER_THREAD];
+  pool_unit *pool = (pool_unit *)(is_v ? P.v_pool : P.k_pool) + (size_t)base * P.frame_units;
+  // moves of survivors come first in the list (ascending candidate order), the new frames last; the prefetched
+  // new frames are stored after all of them (a new frame's slot may still hold a survivor that has to move)
+  const int n_pref = pf_min(P.n_new, POOL_PREFETCH);
+  int n_moves_loop = n_moves;
+  for (int j = 0; j < n_pref; ++j) n_moves_loop -= s_dest[n_old + j] >= 0 ? 1 : 0;
+  if (P.n_new > POOL_PREFETCH) n_moves_loop = n_moves;        // more new frames than registers: the general loop takes them all
+  for (int m0 = 0; m0 < n_moves_loop; m0 += POOL_MOVE_BATCH) {
+    pool_unit r[POOL_MOVE_BATCH][POOL_UNITS_PER_THREAD];
 #pragma unroll
     for (int b = 0; b < POOL_MOVE_BATCH; ++b) {
-      const int src = s_move_src[pf_min(m0 + b, n_moves - 1)];
-      const uint4 *from_pool = pool + (size_t)pf_max(src, 0) * P.frame_units;
-      const uint4 *from_new = fresh + (size_t)pf_max(-src - 1, 0) * new_frame_units;
+      const int src = s_move_src[pf_min(m0 + b, n_moves_loop - 1)];
+      const pool_unit *from_pool = pool + (size_t)pf_max(src, 0) * P.frame_units;
+      const pool_unit *from_new = fresh + (size_t)pf_max(-src - 1, 0) * new_frame_units;
 #pragma unroll
       for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u) r[b][u] = src >= 0 ? from_pool[unit_c[u]] : from_new[fresh_off[u]];
     }
 #pragma unroll
     for (int b = 0; b < POOL_MOVE_BATCH; ++b) {
-      if (m0 + b < n_moves) {
-        uint4 *dp = pool + (size_t)s_move_dst[m0 + b] * P.frame_units;
+      if (m0 + b < n_moves_loop) {
+        pool_unit *dp = pool + (size_t)s_move_dst[m0 + b] * P.frame_units;
 #pragma unroll
         for (int u = 0; u < POOL_UNITS_PER_THREAD; ++u)
           if (valid[u]) dp[unit_c[u]] = r[b][u];
       }
     }
+  }
+
+  if (P.n_new <= POOL_PREFETCH) {
+    auto put = [&](int j, const pool_unit &a, const pool_unit &b) {
+      const int d = j < P.n_new ? s_dest[n_old + j] : -1;
+      if (d >= 0) {
+        pool_unit *dp = pool + (size_t)d * P.frame_units;
+        if (valid[0]) dp[unit_c[0]] = a;
+        if (valid[1]) dp[unit_c[1]] = b;
+      }
+    };
+    put(0, nf00, nf01);
+    put(1, nf10, nf11);
+    put(2, nf20, nf21);
+    put(3, nf30, nf31);
   }
 
   // ---- tables: written by the last workgroup of this head to arrive, after every workgroup of the
