@@ -16,6 +16,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.jo
 
 
 def build(verbose=False, extra=()):
+    """extra: more hipcc flags; PF_HIPCC_FLAGS in the environment adds to them (e.g. -DPF_STRICT_FENCES=1: release
+    fences in front of the cross-workgroup arrival counters, the form the memory model asks for)."""
+    extra = list(extra) + os.environ.get("PF_HIPCC_FLAGS", "").split()
     objs = []
     procs = []
     for src in SOURCES:

@@ -20,6 +20,9 @@
 #include <stddef.h>
 #include <stdlib.h>
 #include "pf_internal.h"
+#ifndef PF_STRICT_FENCES
+#define PF_STRICT_FENCES 0
+#endif
 #include <mutex>
 #include <utility>
 
@@ -77,7 +80,8 @@ __device__ __forceinline__ float partner_sum(float x) {
 // Partial results cross workgroups that may run on different dies, each with its own L2.  They are written
 // and read with device-scope (relaxed atomic) accesses, which go through to the memory side that all dies
 // share; no L2 write-back fence is needed, only the wait for the stores' completion before the arrival
-// counter is bumped.
+// counter is bumped.  Building with -DPF_STRICT_FENCES=1 adds the release fence the memory model asks for in
+// front of every arrival (here and in the pool append): the known-correct form, measured against this one.
 __device__ __forceinline__ void st_dev2(float *p, float a, float b) {
   const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
   __hip_atomic_store((unsigned long long *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -425,9 +429,16 @@ __device__ __forceinline__ void attn_epilogue(const AttnParams &P, const PfWorkI
     for (int e = tid; e < 2 * BQ; e += NT) st_dev1(pm + e, sM[e]);      // sM and sL are adjacent
   }
   __builtin_amdgcn_s_waitcnt(0);             // this wave's partial stores have completed
+#if PF_STRICT_FENCES
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // the memory model's own publication: release before the arrival
+#endif
   __syncthreads();
   if (tid == 0) {
+#if PF_STRICT_FENCES
+    const int arrived = __hip_atomic_fetch_add(&P.counters[it.group], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+#else
     const int arrived = atomicAdd(&P.counters[it.group], 1);
+#endif
     *sFlagp = (arrived == it.nseg - 1) ? 1 : 0;
     if (*sFlagp) P.counters[it.group] = 0;     // ready for the next launch on this index
   }

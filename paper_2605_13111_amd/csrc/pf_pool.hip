@@ -7,6 +7,9 @@
 // frames in order, so all reads and writes of one byte range are issued by one thread in program
 // order: no synchronisation between workgroups is needed and the copy streams at HBM speed.
 #include "pf_internal.h"
+#ifndef PF_STRICT_FENCES
+#define PF_STRICT_FENCES 0   // 1: release fence in front of every arrival counter (the memory model's own form)
+#endif
 
 typedef __attribute__((ext_vector_type(4))) unsigned int pool_unit;   // one 16-byte unit of payload (a native vector: arrays of it stay in registers)
 constexpr int POOL_THREADS = 256;
@@ -232,9 +235,16 @@ __global__ __launch_bounds__(POOL_THREADS) __attribute__((amdgpu_waves_per_eu(1,
   // whole L2 once per workgroup).  The arrival comes after the payload on purpose: atomics and loads return
   // in order, so an early arrival would hold up the loads behind the atomics.  Every head's counter sits in a
   // cache line of its own (PF_SYNC_STRIDE), so the arrivals of different heads do not queue behind each other. ----
+#if PF_STRICT_FENCES
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+#endif
   __syncthreads();
   if (tid == 0) {
+#if PF_STRICT_FENCES
+    const int arrived = __hip_atomic_fetch_add(&P.sync[h * PF_SYNC_STRIDE], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+#else
     const int arrived = atomicAdd(&P.sync[h * PF_SYNC_STRIDE], 1);
+#endif
     s_last = (arrived == 2 * P.blocks_per_head - 1) ? 1 : 0;
   }
   __syncthreads();
