@@ -42,6 +42,9 @@ def parse():
                          "[tokens][heads][D], through the strided entry point")
     ap.add_argument("--cpu-rows", type=int, default=3072, help="query rows per head of layer 0 timed on the CPU oracle")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--block-trace", action="store_true",
+                    help="after the timed steps, run one more attention launch per layer with the library's per-workgroup "
+                         "diagnostics on and report how busy each compute unit's resident workgroup was (cu_busy)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="also run one plain device-to-device copy of this many MiB (a dispatch of known size "
                          "against which hardware traffic counters are scaled)")
@@ -206,6 +209,28 @@ def main():
                         "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": round(float(np.sum(append_bytes)) / (float(np.sum(append_ms)) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
     }
+
+    if args.block_trace:
+        # one resident workgroup per compute unit: ticks (10 ns) inside work items over the launch's span
+        trace = torch.zeros(4 * 1024, dtype=torch.int64, device=dev)
+        B.pf_set_block_trace(trace)
+        fracs, spans = [], []
+        for (pool, index, q, k_cur, v_cur, out) in layers:
+            trace.zero_()
+            attn_fwd(pool, index, q, k_cur, v_cur, out, workspace)
+            torch.cuda.synchronize()
+            t = trace.cpu().numpy().reshape(-1, 4)
+            t = t[t[:, 3] > 0]
+            span = float(t[:, 2].max() - t[:, 1].min())
+            fracs.append(t[:, 0] / span)
+            spans.append(span * 1e-2)
+        B.pf_set_block_trace(None)
+        allf = np.concatenate(fracs)
+        result["cu_busy"] = {"what": "fraction of the launch's span (first item start to last item end over all workgroups) that each "
+                                     "resident workgroup (one per compute unit) spent inside work items, over %d launch(es)" % len(layers),
+                             "workgroups_per_launch": int(len(fracs[0])), "mean": round(float(allf.mean()), 4),
+                             "min": round(float(allf.min()), 4), "p05": round(float(np.percentile(allf, 5)), 4),
+                             "max": round(float(allf.max()), 4), "mean_span_us": round(float(np.mean(spans)), 1)}
 
     # ---------------------------------------------------------------- cpu_baseline: the oracle on a bounded sample
     if not args.no_cpu:

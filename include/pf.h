@@ -203,6 +203,14 @@ int pf_plan_segments(const pf_pool *pool, int T, int q_tokens, int32_t *seg_tile
  * queries); an index must be rebuilt after a change.  Not synchronised with calls running on other threads. */
 int pf_set_tuning(int attn_variant, int attn_queue, int seg_tiles, int plan_uniform);
 
+/* Diagnostics (process-wide, off by default): while a buffer is set, every work-queue launch of the pipelined
+ * attention kernel (variant 1) makes each of its resident workgroups -- one per compute unit -- write four int64 words
+ * at dev_buffer + 32 * workgroup: ticks of the device's constant 100 MHz clock spent inside work items, the
+ * start of its first item, the end of its last item, and the number of items it ran.  A launch with more
+ * resident workgroups than bytes / 32 writes nothing.  Each launch overwrites the last one's figures; NULL switches
+ * it off.  The buffer must stay valid while launches that were enqueued with it may run. */
+int pf_set_block_trace(void *dev_buffer, size_t bytes);
+
 /* ---- the hot path -------------------------------------------------------- */
 
 /* Empty the pool: T = 0, n_frames = 0, frame_ids = -1, frame_score = 0,

@@ -17,7 +17,8 @@ PF_SYNC_STRIDE = 32            # int32 words between the per-head counters of pf
 
 EXPORTS = ["pf_index_work_bytes", "pf_attn_workspace_bytes", "pf_selected_count", "pf_retained_count", "pf_plan_segments",
            "pf_pool_reset", "pf_cache_append", "pf_cache_append_strided", "pf_build_index", "pf_ragged_attn_fwd",
-           "pf_ragged_attn_fwd_strided", "pf_classify_heads", "pf_status_string", "pf_set_tuning", "pf_index_status_dev", "pf_ragged_attn_fwd_static"]
+           "pf_ragged_attn_fwd_strided", "pf_classify_heads", "pf_status_string", "pf_set_tuning", "pf_index_status_dev", "pf_ragged_attn_fwd_static",
+           "pf_set_block_trace"]
 
 
 class pf_head_policy(ctypes.Structure):
@@ -85,6 +86,8 @@ def lib():
         L.pf_ragged_attn_fwd_static.argtypes = [P(pf_pool), P(pf_index), V, V, V, V, I, ctypes.c_float, V]
         L.pf_classify_heads.restype = I
         L.pf_classify_heads.argtypes = [V, I, I, I, ctypes.c_double, ctypes.c_double, V, V, V, V]
+        L.pf_set_block_trace.restype = I
+        L.pf_set_block_trace.argtypes = [V, ctypes.c_size_t]
         L.pf_set_tuning.restype = I
         L.pf_set_tuning.argtypes = [I, I, I, I]
         L.pf_index_status_dev.restype = V
@@ -124,6 +127,15 @@ def make_policy(p):
 def pf_set_tuning(attn_variant=-1, attn_queue=-1, seg_tiles=-1, plan_uniform=-1):
     """Process-wide tuning switches; -1 leaves a switch unchanged."""
     _check(lib().pf_set_tuning(int(attn_variant), int(attn_queue), int(seg_tiles), int(plan_uniform)), "pf_set_tuning")
+
+
+def pf_set_block_trace(buffer):
+    """buffer: int64 CUDA tensor of at least 4 words per compute unit, or None to switch the diagnostics off."""
+    if buffer is None:
+        _check(lib().pf_set_block_trace(ctypes.c_void_p(0), 0), "pf_set_block_trace")
+    else:
+        assert buffer.dtype == torch.int64 and buffer.is_contiguous()
+        _check(lib().pf_set_block_trace(_ptr(buffer), buffer.numel() * 8), "pf_set_block_trace")
 
 
 def pf_index_status(index):

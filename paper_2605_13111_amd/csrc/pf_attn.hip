@@ -56,6 +56,9 @@ struct AttnParams {
   // chunk tensors (q, k_cur, v_cur, out): element strides between tokens of a head and between heads
   // (packed [heads][tokens][D]: D and q_tokens*D; the model's [tokens][heads][D]: heads*D and D)
   long long tok_stride, head_stride;
+  // optional diagnostics (pf_set_block_trace): per resident workgroup {busy, first start, last end, items}, in ticks of the
+  // constant 100 MHz clock; null = off
+  long long *block_trace;
 };
 
 template <class T>
@@ -711,6 +714,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   __shared__ __attribute__((aligned(1024))) char smem[(PP_KSTAGES + PP_VSTAGES) * PP_TILE_BYTES];
   __shared__ int32_t sFlag;
   __shared__ int32_t sNext;
+  __shared__ long long sTrace[4];                              // busy ticks, first start, this item's start, items (thread 0 only)
   char (*sK)[PP_TILE_BYTES] = (char (*)[PP_TILE_BYTES])smem;
   char (*sV)[PP_TILE_BYTES] = sK + PP_KSTAGES;
   const int tid0 = threadIdx.x;
@@ -742,6 +746,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     R.tickets = as_global(R.tickets), R.workspace = as_global(R.workspace);
     return R;
   };
+  if (tid0 == 0) sTrace[0] = sTrace[1] = sTrace[2] = sTrace[3] = 0;
   int hop_v = 0;                               // dies given up so far; kept in a vector register between items
   while (true) {
   asm volatile("" : "+v"(hop_v));
@@ -770,6 +775,11 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   if (item_idx < 0) break;
   const PfWorkItem it = P.items[item_idx];
   if (it.head < 0) continue;
+  if (__builtin_expect(P.block_trace != nullptr, 0) && tid0 == 0) {
+    const long long now = wall_clock64();
+    if (sTrace[3] == 0) sTrace[1] = now;
+    sTrace[2] = now;
+  }
   int tid = tid0;
   asm volatile("" : "+v"(tid));               // per-lane constants are worked out anew for each item, not kept across the loop
   const int lane = tid & 63;
@@ -1094,6 +1104,19 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   __syncthreads();
   const AttnParams Pe = load_params();                         // read again: nothing of it is held through the loop above
   attn_epilogue<D, 1, PP_WAVES>(Pe, it, o, m_run, l_run, (float *)&sK[0][0], &sFlag, tid);
+  if (__builtin_expect(Pe.block_trace != nullptr, 0) && tid0 == 0) {
+    const long long now = wall_clock64();
+    sTrace[0] += now - sTrace[2];
+    sTrace[2] = now;                                           // doubles as "last end"
+    sTrace[3] += 1;
+  }
+  }
+  {
+    long long *bt = load_params().block_trace;
+    if (__builtin_expect(bt != nullptr, 0) && tid0 == 0) {
+      bt = as_global(bt) + (size_t)blockIdx.x * 4;
+      bt[0] = sTrace[0]; bt[1] = sTrace[1]; bt[2] = sTrace[2]; bt[3] = sTrace[3];
+    }
   }
   int32_t *tickets = load_params().tickets;
   if (tickets != nullptr && tid0 == 0) {
@@ -1115,6 +1138,16 @@ static int pp_resident_workgroups() {
     n_cu[dev] = n;
   }
   return n_cu[dev];
+}
+
+// Diagnostics: where the resident workgroups of the pipelined kernel write their busy times (see pf_set_block_trace).
+static long long *g_block_trace = nullptr;
+static size_t g_block_trace_bytes = 0;
+extern "C" int pf_set_block_trace(void *dev_buffer, size_t bytes) {
+  if (dev_buffer && ((((uintptr_t)dev_buffer) & 7u) || bytes < 32)) return PF_ERR_INVALID_ARG;
+  g_block_trace = (long long *)dev_buffer;
+  g_block_trace_bytes = dev_buffer ? bytes : 0;
+  return PF_OK;
 }
 
 static int launch_attn(const AttnParams &P, int head_dim, int variant, int n_blocks, hipStream_t stream) {
@@ -1179,6 +1212,7 @@ static int attn_fwd_impl(const pf_pool *pool, const pf_index *index, const void 
   P.tpf = pool->tokens_per_frame;
   P.q_tokens = q_tokens;
   P.n_qt = n_qt;
+  P.block_trace = (queue && g_block_trace_bytes >= (size_t)pf_min(index->n_blocks, pp_resident_workgroups()) * 32) ? g_block_trace : nullptr;
   P.tok_stride = layout ? layout->token_stride : pool->head_dim;
   P.head_stride = layout ? layout->head_stride : (long long)q_tokens * pool->head_dim;
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)pool->head_dim);
