@@ -645,15 +645,14 @@ constexpr int pp_reads_between(int i, int last) {
 
 __device__ __forceinline__ int pp_swz(bool is_v, int row) { return is_v ? ((row & 3) << 2) : (row & 15); }
 
-// Copies this wave's 8 rows (wave*8 ..) of tile kt of one tensor into the stage at LDS pointer `stage`.
-// Returns the number of copy instructions issued (2 when the tile is contiguous in memory, else 8).
-// voff[h]: per-lane source offset inside the 4-row group h of this wave, see pp_group_voff.
+// Per-lane source offset inside a 4-row copy group whose first row is row0: lane i fetches the 16-byte chunk that
+// belongs at bytes 16*i of the group's 1 KB destination (chunk permutation of the tile layouts above).
 template <bool IS_V>
 __device__ __forceinline__ unsigned pp_group_voff(int lane, int row0) {
   const int rr = lane >> 4, p = lane & 15;
   return (unsigned)(rr * 256 + ((p ^ pp_swz(IS_V, row0 + rr)) << 4));
 }
-template <bool IS_V>
+template <bool IS_V, int RPW>
 __device__ __forceinline__ int pp_copy_rows_slow(int kt, const HeadKV &H, char *stage, int wave, int lane) {
   typedef const __attribute__((address_space(1))) void *gptr_t;
   typedef __attribute__((address_space(3))) void *lptr_t;
@@ -661,8 +660,8 @@ __device__ __forceinline__ int pp_copy_rows_slow(int kt, const HeadKV &H, char *
   const int last = H.lkv - 1 - kt * PF_BK;
   asm volatile("" : "+v"(lane));                    // rare path: its per-lane offsets are worked out here, not held in registers through the loop
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    const int row = wave * 8 + r;
+  for (int r = 0; r < RPW; ++r) {
+    const int row = wave * RPW + r;
     const int t = kt * PF_BK + pf_min(row, last);                 // rows past the end re-read the last key
     const bool in_chunk = t >= H.hist_tokens;
     const int th = in_chunk ? 0 : t;
@@ -673,7 +672,7 @@ __device__ __forceinline__ int pp_copy_rows_slow(int kt, const HeadKV &H, char *
     const unsigned off = (unsigned)((((lane >> 2) ^ pp_swz(IS_V, row)) << 4) | ((lane & 3) << 2));
     __builtin_amdgcn_global_load_lds((gptr_t)(b + off), (lptr_t)(stage + row * 256), 4, 0, 0);
   }
-  return 8;
+  return RPW;
 }
 
 // Request fragment I of a matrix phase (see the kernel): ak / av = this lane's K / V^T base address in the stage.
@@ -701,16 +700,177 @@ __device__ __forceinline__ void pp_wait_frag(u32x2 (&vl)[16], u32x2 (&vh)[16], u
   __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int D>
-__global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams) {
+// ---- 4 waves x 64 query rows: one instruction stream per SIMD that carries the MFMAs of two half tiles (32 keys)
+// and the softmax of the half tile between them (see the kernel).  A half step's operand fragments, in the order they
+// are consumed: V^T of the previous half tile (8, if the half step has a PV part), K of the next half tile (8, if it
+// has a QK part), and, when it prefetches, the first PP_RING V^T fragments of its own half tile, which the following
+// half step consumes first.
+template <bool PV, bool QK, bool PRE>
+struct W64Stream {
+  static constexpr int NV = PV ? 8 : 0, NK = QK ? 8 : 0, NC = NV + NK, L = NC + (PRE ? PP_RING : 0);
+  static constexpr int NSLOT = NC > 0 ? 2 * NC : 1;              // MFMA slots: two per fragment (the query blocks)
+  static constexpr int kind(int p) { return p < NV ? 0 : p < NC ? 1 : 2; }
+  static constexpr int idx(int p) { return p < NV ? p : p < NC ? p - NV : p - NC; }
+  static constexpr int reads(int p) { return kind(p) == 1 ? 1 : 2; }
+  // LDS reads requested after fragment p's at the time its first MFMA is issued
+  static constexpr int wait_n(int p) {
+    int n = 0;
+    for (int q = p + 1; q < p + PP_RING && q < L; ++q) n += reads(q);
+    return n;
+  }
+};
+// The softmax of one half tile (16 scores per lane and query block) as 65 small steps that are dealt out between the
+// MFMAs in proportion to their instruction counts: 0..15 running maxima (two scores each; two chains per query block
+// take turns, block 0 first), 16 the check against the reference maximum, which moves only when a score exceeds it by
+// the lazy margin (then, and only then, the two lanes of a query column exchange their maxima), then for each of 16
+// score pairs three steps a few instructions apart, so that none waits for the one before: "scale" (2 instructions),
+// "exp2" (2), "add to the row sum, round to bf16" (3).
+constexpr int W64_NSTEP = 65;
+constexpr int W64_BSTEP0 = 17;                                   // first step of the exp2 part
+// step W64_BSTEP0 + t -> kind (0 scale, 1 exp2, 2 sum and round) * 16 + score pair: pair u is scaled at time u, goes
+// through exp2 at time u + 1 and is summed at time u + 2
+constexpr int w64_bstep(int t) {
+  int n = 0;
+  for (int tau = 0; tau < 18; ++tau)
+    for (int kind = 0; kind < 3; ++kind) {
+      const int u = tau - kind;
+      if (u < 0 || u > 15) continue;
+      if (n == t) return kind * 16 + u;
+      ++n;
+    }
+  return -1;
+}
+constexpr int w64_step_weight(int k) {
+  if (k < 16) return 1;
+  if (k == 16) return 6;
+  return w64_bstep(k - W64_BSTEP0) / 16 == 2 ? 3 : 2;
+}
+constexpr int w64_weight_before(int k) {
+  int w = 0;
+  for (int i = 0; i < k; ++i) w += w64_step_weight(i);
+  return w;
+}
+constexpr int w64_first_step(int slot, int nslot) {
+  const int total = w64_weight_before(W64_NSTEP);
+  for (int k = 0; k < W64_NSTEP; ++k)
+    if (w64_weight_before(k) * nslot >= slot * total) return k;
+  return W64_NSTEP;
+}
+// The 64-row form keeps its long-lived MFMA operands in accumulation registers that the compiler never sees: the output
+// accumulators in a64..a191 (block n = 4*qb + db in a[64 + 16*n ..]) and the Q^T fragments in a192..a255 (fragment
+// n = 8*qb + ks in a[192 + 4*n ..]) for the whole work item; the scores are ordinary vector registers, where the softmax
+// reads them without copies.  All MFMAs of that form are asm statements that name these registers.  (Left to the
+// compiler, a kernel that may use all 512 registers gets every MFMA result in accumulation registers, pays a copy per
+// score and keeps moving the accumulators around.)  This only works because the compiler itself stays out of a64..a255
+// in that kernel: it has no MFMA builtin there, the library is built with spilling of vector registers into
+// accumulation registers switched off (-mllvm -amdgpu-spill-vgpr-to-agpr=0), the few values it still parks there go to
+// the lowest registers, and the build reads the listing and fails if any instruction of the compiler's own touches a
+// register from a32 up (build.py).
+// The compiler does not know these statements are MFMAs and adds no wait states around them: the distances the
+// hardware needs between an MFMA and a dependent instruction are kept by the order of the stream (see the kernel), and
+// no operand of such a statement is written by a vector instruction right in front of it.
+#define PF_A10(b) "a" #b "0", "a" #b "1", "a" #b "2", "a" #b "3", "a" #b "4", "a" #b "5", "a" #b "6", "a" #b "7", "a" #b "8", "a" #b "9"
+#define PF_CLOBBER_A64_A191                                                                                                  \
+  "a64", "a65", "a66", "a67", "a68", "a69", PF_A10(7), PF_A10(8), PF_A10(9), PF_A10(10), PF_A10(11), PF_A10(12), PF_A10(13), \
+      PF_A10(14), PF_A10(15), PF_A10(16), PF_A10(17), PF_A10(18), "a190", "a191"
+#define PF_CLOBBER_A192_A255 "a192", "a193", "a194", "a195", "a196", "a197", "a198", "a199", PF_A10(20), PF_A10(21), PF_A10(22), PF_A10(23), PF_A10(24), "a250", "a251", "a252", "a253", "a254", "a255"
+template <int N> __device__ __forceinline__ void w64_mfma_o(u32x4 a, bf16x8 b);     // O^T block n += a . b
+template <int N> __device__ __forceinline__ void w64_mfma_s(f32x16 &acc, u32x4 a);  // acc += a . Q^T fragment n
+template <int N> __device__ __forceinline__ void w64_mfma_s0(f32x16 &acc, u32x4 a); // acc  = a . Q^T fragment n
+template <int N> __device__ __forceinline__ void w64_set_q(u32x4 q);                // Q^T fragment n = q
+template <int N> __device__ __forceinline__ f32x16 w64_get_o();                     // O^T block n
+#define PF_W64_O(N, R0, R1, R2, R3, R4, R5, R6, R7, R8, R9, R10, R11, R12, R13, R14, R15)                                    \
+  template <> __device__ __forceinline__ void w64_mfma_o<N>(u32x4 a, bf16x8 b) {                                             \
+    asm volatile("v_mfma_f32_32x32x16_bf16 a[" #R0 ":" #R15 "], %0, %1, a[" #R0 ":" #R15 "]" : : "v"(a), "v"(b)              \
+                 : PF_CLOBBER_A64_A191);                                                                                     \
+  }                                                                                                                          \
+  template <> __device__ __forceinline__ f32x16 w64_get_o<N>() {                                                             \
+    float r[16];                                                                                                             \
+    asm volatile("v_accvgpr_read_b32 %0, a" #R0 "\n\tv_accvgpr_read_b32 %1, a" #R1 "\n\tv_accvgpr_read_b32 %2, a" #R2       \
+                 "\n\tv_accvgpr_read_b32 %3, a" #R3 "\n\tv_accvgpr_read_b32 %4, a" #R4 "\n\tv_accvgpr_read_b32 %5, a" #R5    \
+                 "\n\tv_accvgpr_read_b32 %6, a" #R6 "\n\tv_accvgpr_read_b32 %7, a" #R7 "\n\tv_accvgpr_read_b32 %8, a" #R8    \
+                 "\n\tv_accvgpr_read_b32 %9, a" #R9 "\n\tv_accvgpr_read_b32 %10, a" #R10 "\n\tv_accvgpr_read_b32 %11, a" #R11 \
+                 "\n\tv_accvgpr_read_b32 %12, a" #R12 "\n\tv_accvgpr_read_b32 %13, a" #R13                                  \
+                 "\n\tv_accvgpr_read_b32 %14, a" #R14 "\n\tv_accvgpr_read_b32 %15, a" #R15                                  \
+                 : "=v"(r[0]), "=v"(r[1]), "=v"(r[2]), "=v"(r[3]), "=v"(r[4]), "=v"(r[5]), "=v"(r[6]), "=v"(r[7]), "=v"(r[8]), \
+                   "=v"(r[9]), "=v"(r[10]), "=v"(r[11]), "=v"(r[12]), "=v"(r[13]), "=v"(r[14]), "=v"(r[15]));                \
+    f32x16 v;                                                                                                                \
+    _Pragma("unroll") for (int i = 0; i < 16; ++i) v[i] = r[i];                                                             \
+    return v;                                                                                                                \
+  }
+PF_W64_O(0, 64, 65, 66, 67, 68, 69, 70, 71, 72, 73, 74, 75, 76, 77, 78, 79)
+PF_W64_O(1, 80, 81, 82, 83, 84, 85, 86, 87, 88, 89, 90, 91, 92, 93, 94, 95)
+PF_W64_O(2, 96, 97, 98, 99, 100, 101, 102, 103, 104, 105, 106, 107, 108, 109, 110, 111)
+PF_W64_O(3, 112, 113, 114, 115, 116, 117, 118, 119, 120, 121, 122, 123, 124, 125, 126, 127)
+PF_W64_O(4, 128, 129, 130, 131, 132, 133, 134, 135, 136, 137, 138, 139, 140, 141, 142, 143)
+PF_W64_O(5, 144, 145, 146, 147, 148, 149, 150, 151, 152, 153, 154, 155, 156, 157, 158, 159)
+PF_W64_O(6, 160, 161, 162, 163, 164, 165, 166, 167, 168, 169, 170, 171, 172, 173, 174, 175)
+PF_W64_O(7, 176, 177, 178, 179, 180, 181, 182, 183, 184, 185, 186, 187, 188, 189, 190, 191)
+#undef PF_W64_O
+#define PF_W64_Q(N, R0, R1, R2, R3)                                                                                          \
+  template <> __device__ __forceinline__ void w64_mfma_s<N>(f32x16 & acc, u32x4 a) {                                         \
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, a[" #R0 ":" #R3 "], %0" : "+v"(acc) : "v"(a));                            \
+  }                                                                                                                          \
+  template <> __device__ __forceinline__ void w64_mfma_s0<N>(f32x16 & acc, u32x4 a) {                                        \
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, a[" #R0 ":" #R3 "], 0" : "=&v"(acc) : "v"(a));                            \
+  }                                                                                                                          \
+  template <> __device__ __forceinline__ void w64_set_q<N>(u32x4 q) {                                                        \
+    asm volatile("v_accvgpr_write_b32 a" #R0 ", %0\n\tv_accvgpr_write_b32 a" #R1 ", %1\n\tv_accvgpr_write_b32 a" #R2        \
+                 ", %2\n\tv_accvgpr_write_b32 a" #R3 ", %3"                                                                  \
+                 : : "v"(q[0]), "v"(q[1]), "v"(q[2]), "v"(q[3]) : PF_CLOBBER_A192_A255);                                     \
+  }
+PF_W64_Q(0, 192, 193, 194, 195) PF_W64_Q(1, 196, 197, 198, 199) PF_W64_Q(2, 200, 201, 202, 203) PF_W64_Q(3, 204, 205, 206, 207)
+PF_W64_Q(4, 208, 209, 210, 211) PF_W64_Q(5, 212, 213, 214, 215) PF_W64_Q(6, 216, 217, 218, 219) PF_W64_Q(7, 220, 221, 222, 223)
+PF_W64_Q(8, 224, 225, 226, 227) PF_W64_Q(9, 228, 229, 230, 231) PF_W64_Q(10, 232, 233, 234, 235) PF_W64_Q(11, 236, 237, 238, 239)
+PF_W64_Q(12, 240, 241, 242, 243) PF_W64_Q(13, 244, 245, 246, 247) PF_W64_Q(14, 248, 249, 250, 251) PF_W64_Q(15, 252, 253, 254, 255)
+#undef PF_W64_Q
+// a64..a191 = 0, and a64..a191 *= alpha (a64..a127: query block 0, a128..a191: query block 1): a loop over the register
+// NUMBER cannot be written (no indirect access to accumulation registers), so the text is spelled out, ten registers (one decade of numbers) at a time
+#define PF_W64_Z10(b) "v_accvgpr_write_b32 a" #b "0, 0\n\tv_accvgpr_write_b32 a" #b "1, 0\n\tv_accvgpr_write_b32 a" #b "2, 0\n\tv_accvgpr_write_b32 a" #b "3, 0\n\tv_accvgpr_write_b32 a" #b "4, 0\n\tv_accvgpr_write_b32 a" #b "5, 0\n\tv_accvgpr_write_b32 a" #b "6, 0\n\tv_accvgpr_write_b32 a" #b "7, 0\n\tv_accvgpr_write_b32 a" #b "8, 0\n\tv_accvgpr_write_b32 a" #b "9, 0\n\t"
+__device__ __forceinline__ void w64_zero_o() {
+  asm volatile("v_accvgpr_write_b32 a64, 0\n\tv_accvgpr_write_b32 a65, 0\n\tv_accvgpr_write_b32 a66, 0\n\tv_accvgpr_write_b32 a67, 0\n\t"
+               "v_accvgpr_write_b32 a68, 0\n\tv_accvgpr_write_b32 a69, 0\n\t"
+               PF_W64_Z10(7) PF_W64_Z10(8) PF_W64_Z10(9) PF_W64_Z10(10) PF_W64_Z10(11) PF_W64_Z10(12) PF_W64_Z10(13) PF_W64_Z10(14)
+               PF_W64_Z10(15) PF_W64_Z10(16) PF_W64_Z10(17) PF_W64_Z10(18) "v_accvgpr_write_b32 a190, 0\n\tv_accvgpr_write_b32 a191, 0"
+               : : : PF_CLOBBER_A64_A191);
+}
+#undef PF_W64_Z10
+#define PF_W64_R1(r, al) "v_accvgpr_read_b32 %2, a" #r "\n\tv_mul_f32 %2, %2, %" #al "\n\tv_accvgpr_write_b32 a" #r ", %2\n\t"
+#define PF_W64_R10(b, al) PF_W64_R1(b##0, al) PF_W64_R1(b##1, al) PF_W64_R1(b##2, al) PF_W64_R1(b##3, al) PF_W64_R1(b##4, al) PF_W64_R1(b##5, al) PF_W64_R1(b##6, al) PF_W64_R1(b##7, al) PF_W64_R1(b##8, al) PF_W64_R1(b##9, al)
+__device__ __forceinline__ void w64_rescale(float al0, float al1) {
+  float t;
+  asm volatile("s_nop 15\n\ts_nop 15\n\t"                          // the last MFMA into the accumulators has written them back
+               PF_W64_R1(64, 0) PF_W64_R1(65, 0) PF_W64_R1(66, 0) PF_W64_R1(67, 0) PF_W64_R1(68, 0) PF_W64_R1(69, 0)
+               PF_W64_R10(7, 0) PF_W64_R10(8, 0) PF_W64_R10(9, 0) PF_W64_R10(10, 0) PF_W64_R10(11, 0)
+               PF_W64_R1(120, 0) PF_W64_R1(121, 0) PF_W64_R1(122, 0) PF_W64_R1(123, 0) PF_W64_R1(124, 0) PF_W64_R1(125, 0) PF_W64_R1(126, 0) PF_W64_R1(127, 0)
+               PF_W64_R1(128, 1) PF_W64_R1(129, 1)
+               PF_W64_R10(13, 1) PF_W64_R10(14, 1) PF_W64_R10(15, 1) PF_W64_R10(16, 1) PF_W64_R10(17, 1) PF_W64_R10(18, 1)
+               PF_W64_R1(190, 1) PF_W64_R1(191, 1) "s_nop 7"
+               : "+v"(al0), "+v"(al1), "=&v"(t) : : PF_CLOBBER_A64_A191);
+}
+#undef PF_W64_R10
+#undef PF_W64_R1
+template <int N>
+__device__ __forceinline__ void pp_wait_lgkm() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8));                 // lgkmcnt(N), the other counters untouched
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void pf_attn_pp_kernel(AttnParams) {
   static_assert(D == 128, "tile layouts are written for 256-byte rows");
+  static_assert(NW == 8 || NW == 4, "8 waves x 32 query rows, or 4 waves x 64");
+  constexpr int RPW = PF_BK / NW;                              // rows of every tile that one wave copies
+  constexpr int NG = RPW / 4;                                  // ... in groups of four rows, one copy instruction each
+  constexpr int NQB = 256 / (NW * 32);                         // 32-row query blocks per wave
   constexpr int BK = PF_BK;
   constexpr int NKS = D / 16, NDB = D / 32;
   typedef const __attribute__((address_space(1))) void *gptr_t;
   typedef __attribute__((address_space(3))) void *lptr_t;
 
   // K ring, then V ring; the epilogue reuses the same memory to stage the output rows
-  static_assert((PP_KSTAGES + PP_VSTAGES) * PP_TILE_BYTES >= attn_stage_floats(PP_WAVES * 32, D) * 4, "output staging fits");
+  static_assert((PP_KSTAGES + PP_VSTAGES) * PP_TILE_BYTES >= attn_stage_floats(256, D) * 4, "output staging fits");
   __shared__ __attribute__((aligned(1024))) char smem[(PP_KSTAGES + PP_VSTAGES) * PP_TILE_BYTES];
   __shared__ int32_t sFlag;
   __shared__ int32_t sNext;
@@ -788,9 +948,9 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   const int l32 = lane & 31, g = lane >> 5;
   HeadKV H;
   attn_setup_head<D>(P, it, H, tid);
-  f32x16 o[1][NDB];
-  float m_run[1], l_run[1];
-  attn_zero<D, 1>(o, m_run, l_run);
+  f32x16 o[NQB][NDB];
+  float m_run[NQB], l_run[NQB];
+  attn_zero<D, NQB>(o, m_run, l_run);
   const float c = P.scale_log2;
   const float thr = ATT_LAZY_LOG2 / c;
 
@@ -808,43 +968,52 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     const int c0 = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
     av = ldsV + rowv * 256 + ((c0 ^ pp_swz(true, rowv)) << 4) + 8 * (lane & 1);
   }
-  // per-lane source offsets inside a 4-row copy group; the wave's second group (rows + 4) differs in one bit
-  // for K and not at all for V
-  const unsigned vofK0 = pp_group_voff<false>(lane, wave * 8), vofK1 = vofK0 ^ 64u, vofV = pp_group_voff<true>(lane, wave * 8);
-  const int wrow_bytes = wave * 8 * 256;                       // this wave's first row inside a tile
+  // per-lane source offsets inside a 4-row copy group.  The wave's later groups (rows + 4, + 8, + 12) permute the
+  // K chunks by one more bit each and the V chunks not at all
+  const unsigned vofK0 = pp_group_voff<false>(lane, wave * RPW), vofV = pp_group_voff<true>(lane, wave * RPW);
+  const int wrow_bytes = wave * RPW * 256;                     // this wave's first row inside a tile
 
-  // One 4-row group: h = 0, 1 (K), 2, 3 (V).  The copies are buffer loads: the tile's first row is the base of a
-  // 16 KB buffer descriptor (scalar registers), the wave's rows are a scalar offset, the lane's chunk a 32-bit
-  // vector offset that never changes, and the second group is the instruction's immediate offset (it moves the
-  // LDS destination along with the source).  Next to MFMAs this form costs almost nothing, whereas a global
-  // load with a 64-bit address per lane held up the SIMD for ~65 cycles per instruction (measured).
-  auto copy_group_at = [&](const __bf16 *kbase, const __bf16 *vbase, int snk, int snv, int h) {
+  // One 4-row group gi of K or of V.  The copies are buffer loads: the tile's first row is the base of a 16 KB
+  // buffer descriptor (scalar registers), the wave's rows are a scalar offset, the lane's chunk a 32-bit vector
+  // offset, and the group is the instruction's immediate offset (it moves the LDS destination along with the
+  // source).  Next to MFMAs this form costs almost nothing, whereas a global load with a 64-bit address per lane
+  // held up the SIMD for ~65 cycles per instruction (measured).
+  auto copy_group_at = [&](const __bf16 *kbase, const __bf16 *vbase, int snk, int snv, auto is_v, auto gidx) __attribute__((always_inline)) {
     constexpr unsigned RSRC_FLAGS = 0x00020000u;               // raw buffer, 32-bit data format
-    if (h < 2) {
+    constexpr int GI = decltype(gidx)::value;
+    if constexpr (!decltype(is_v)::value) {
       const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)kbase, 0, PP_TILE_BYTES, RSRC_FLAGS);
-      lptr_t dst = (lptr_t)(&sK[snk][wrow_bytes]);
-      if (h == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofK0, wrow_bytes, 0, 0);
-      else __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofK1, wrow_bytes, 1024, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lptr_t)(&sK[snk][wrow_bytes]), 16, vofK0 ^ (unsigned)(GI << 6), wrow_bytes, GI * 1024, 0);
     } else {
       const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)vbase, 0, PP_TILE_BYTES, RSRC_FLAGS);
-      lptr_t dst = (lptr_t)(&sV[snv][wrow_bytes]);
-      if (h == 2) __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofV, wrow_bytes, 0, 0);
-      else __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vofV, wrow_bytes, 1024, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lptr_t)(&sV[snv][wrow_bytes]), 16, vofV, wrow_bytes, GI * 1024, 0);
     }
   };
-  auto copy_group = [&](const TileSrc &src, int snk, int snv, int h) { copy_group_at(src.kb, src.vb, snk, snv, h); };
+  // a whole contiguous tile: K groups, then V groups
+  auto copy_tile_dense = [&](const __bf16 *kbase, const __bf16 *vbase, int snk, int snv) __attribute__((always_inline)) {
+    static_for<0, NG>([&](auto gi) { copy_group_at(kbase, vbase, snk, snv, TagF(), gi); });
+    static_for<0, NG>([&](auto gi) { copy_group_at(kbase, vbase, snk, snv, TagT(), gi); });
+  };
   // The same for a chunk tile whose token rows are cur_stride elements apart (the model's [tokens][heads][D]
-  // layout): the lane's row is part of its vector offset, the wave's first row and the second group are scalar
-  // offsets, and the second group's LDS destination moves by hand.
+  // layout): the lane's row is part of its vector offset, the wave's first row and the group are scalar
+  // offsets, and the group's LDS destination moves by hand.
   const unsigned row_b = (unsigned)(H.cur_stride * 2);         // bytes between chunk token rows (< 2^25, checked on the host)
-  const unsigned sofK0 = (unsigned)(((vofK0 & 0xffu) + (lane >> 4) * row_b)), sofK1 = (unsigned)(((vofK1 & 0xffu) + (lane >> 4) * row_b));
-  const unsigned sofV = (unsigned)(((vofV & 0xffu) + (lane >> 4) * row_b));
-  auto copy_group_strided = [&](const TileSrc &src, int snk, int snv, int h) {
+  auto copy_tile_strided = [&](const TileSrc &src, int snk, int snv) __attribute__((always_inline)) {
     constexpr unsigned RSRC_FLAGS = 0x00020000u;
-    const unsigned soff = (unsigned)(wave * 8 + 4 * (h & 1)) * row_b;
-    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)(h < 2 ? src.kb : src.vb), 0, (int)(PF_BK * row_b), RSRC_FLAGS);
-    lptr_t dst = h < 2 ? (lptr_t)(&sK[snk][wrow_bytes + (h & 1) * 1024]) : (lptr_t)(&sV[snv][wrow_bytes + (h & 1) * 1024]);
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, h == 0 ? sofK0 : h == 1 ? sofK1 : sofV, soff, 0, 0);
+    const unsigned lrow = (unsigned)(lane >> 4) * row_b;
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc((void *)src.kb, 0, (int)(PF_BK * row_b), RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)src.vb, 0, (int)(PF_BK * row_b), RSRC_FLAGS);
+    static_for<0, NG>([&](auto gi) {
+      constexpr int GI = decltype(gi)::value;
+      const unsigned soff = (unsigned)(wave * RPW + 4 * GI) * row_b;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lptr_t)(&sK[snk][wrow_bytes + GI * 1024]), 16,
+                                               ((vofK0 ^ (unsigned)(GI << 6)) & 0xffu) + lrow, soff, 0, 0);
+    });
+    static_for<0, NG>([&](auto gi) {
+      constexpr int GI = decltype(gi)::value;
+      const unsigned soff = (unsigned)(wave * RPW + 4 * GI) * row_b;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lptr_t)(&sV[snv][wrow_bytes + GI * 1024]), 16, (vofV & 0xffu) + lrow, soff, 0, 0);
+    });
   };
   // A tile made of two dense runs (it crosses a frame border): a 4-row group lies in the first run, in the second, or
   // (when the border is not a multiple of 4 rows into the tile) in both, and then each run's lanes copy under their
@@ -854,47 +1023,60 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     int n = 0;
     const __bf16 *ka = src.kb, *va = src.vb, *kb2 = src.kb2, *vb2 = src.vb2;
     const int n1 = src.n1;
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      const int row0 = wave * 8 + (h & 1) * 4;
+    auto one = [&](auto is_v, auto gi) __attribute__((always_inline)) {
+      const int row0 = wave * RPW + decltype(gi)::value * 4;
       if (row0 + 4 <= n1) {
-        copy_group_at(ka, va, snk, snv, h);
+        copy_group_at(ka, va, snk, snv, is_v, gi);
         n += 1;
       } else if (row0 >= n1) {
-        copy_group_at(kb2, vb2, snk, snv, h);
+        copy_group_at(kb2, vb2, snk, snv, is_v, gi);
         n += 1;
       } else {
         int lane_l = lane;
         asm volatile("" : "+v"(lane_l));                        // rare: its lane test is not held in a register through the loop
-        if (row0 + (lane_l >> 4) < n1) copy_group_at(ka, va, snk, snv, h);
-        else copy_group_at(kb2, vb2, snk, snv, h);
+        if (row0 + (lane_l >> 4) < n1) copy_group_at(ka, va, snk, snv, is_v, gi);
+        else copy_group_at(kb2, vb2, snk, snv, is_v, gi);
         n += 2;
       }
-    }
+    };
+    static_for<0, NG>([&](auto gi) { one(TagF(), gi); });
+    static_for<0, NG>([&](auto gi) { one(TagT(), gi); });
     return n;
   };
   // whole tile at once (prologue; tiles that cross a frame border or hold the ragged end go row by row here)
   auto copy_tile_now = [&](int kt, const TilePos &tp, int snk, int snv) -> int {
     const TileSrc src = tile_src(kt, tp, H, D);
     if (src.simple) {
-#pragma unroll
-      for (int h = 0; h < 4; ++h) {
-        if (src.strided) copy_group_strided(src, snk, snv, h);
-        else copy_group(src, snk, snv, h);
-      }
-      return 4;
+      if (src.strided) copy_tile_strided(src, snk, snv);
+      else copy_tile_dense(src.kb, src.vb, snk, snv);
+      return 2 * NG;
     }
-    pp_copy_rows_slow<false>(kt, H, sK[snk], wave, lane);
-    pp_copy_rows_slow<true>(kt, H, sV[snv], wave, lane);
-    return 16;
+    pp_copy_rows_slow<false, RPW>(kt, H, sK[snk], wave, lane);
+    pp_copy_rows_slow<true, RPW>(kt, H, sV[snv], wave, lane);
+    return 2 * RPW;
   };
-  // "Everything but the copies of the last vector phase has landed": at most 4 vector-memory operations may be
-  // outstanding (a contiguous tile's copies).  When the last vector phase sent a tile row by row (16 copies, at
-  // a frame border) this also waits for 12 of those, which were sent a whole matrix phase ago; when it sent
-  // nothing, the older copies are all that is in flight.
-  auto wait_copies = [&](int n) {
-    __builtin_amdgcn_s_waitcnt(0x0F70 | 4);
+  // "Everything but the copies of the last step has landed": at most 2*NG vector-memory operations may be
+  // outstanding (a contiguous tile's copies).  When the last step sent a tile row by row (at a frame border) this
+  // also waits for most of those, which were sent a whole step ago; when it sent nothing, the older copies are all
+  // that is in flight.
+  auto wait_copies = [&](int n) __attribute__((always_inline)) {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * NG));
     if (__builtin_expect(n == 0, 0)) __builtin_amdgcn_s_waitcnt(0x0F70);
+  };
+  // the copy planned for this step (see plan_copy), K into stage snk, V into stage snv; returns the instruction count
+  auto copy_planned = [&](const TileSrc &src, int kt_copy, int snk, int snv) __attribute__((always_inline)) -> int {
+    if (__builtin_expect(src.simple && !src.strided, 1)) {
+      copy_tile_dense(src.kb, src.vb, snk, snv);
+      return 2 * NG;
+    }
+    if (src.simple) {
+      copy_tile_strided(src, snk, snv);
+      return 2 * NG;
+    }
+    if (src.split) return copy_tile_split(src, snk, snv);
+    pp_copy_rows_slow<false, RPW>(kt_copy, H, sK[snk], wave, lane);
+    pp_copy_rows_slow<true, RPW>(kt_copy, H, sV[snv], wave, lane);
+    return 2 * RPW;
   };
 
   // ---- prologue: tiles kt0 .. kt0+2 start travelling, then Q^T is fetched.  Vector-memory operations complete
@@ -910,6 +1092,45 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     tile_pos_advance(pos, H.n_sel, H.tpf);
     copy_tile_now(it.kt0 + 2, pos, 2, 2);
   }
+  // ---- plan of the next copy (made in one vector phase and carried out at the start of the next, so the
+  // scalar load of a frame's slot has a whole tile time to arrive) ----
+  TileSrc nsrc;
+  nsrc.kb = nsrc.vb = nsrc.kb2 = nsrc.vb2 = nullptr;
+  nsrc.simple = nsrc.split = false;
+  nsrc.n1 = 0;
+  int ncopy_kt = -1;                                           // tile planned for the next copy, -1: none
+  int run_left = 0;                                            // tiles after the planned one that continue its source run
+  long long run_step = 0;                                      // elements from one tile of the run to the next
+  auto plan_copy = [&](int kt_target) __attribute__((always_inline)) {
+    if (__builtin_expect(run_left <= 0, 0)) {
+      ncopy_kt = -1;
+      if (kt_target < it.kt1) {
+        tile_pos_advance(pos, H.n_sel, H.tpf);
+        nsrc = tile_src(kt_target, pos, H, D);
+        ncopy_kt = kt_target;
+        if (nsrc.simple) {
+          const int room = pos.j < H.n_sel ? H.tpf - pos.r : H.lkv - kt_target * PF_BK;   // keys from the tile's first row to the run's end
+          run_left = pf_min(room / PF_BK - 1, it.kt1 - 1 - kt_target);
+          run_step = (long long)PF_BK * (pos.j < H.n_sel ? D : H.cur_stride);
+        }
+      }
+    } else {
+      // common case: the tile follows a contiguous tile of the same frame (or of the chunk), is itself whole and
+      // inside it, and belongs to this work item: both sources move on by one tile, no slot lookup
+      --run_left;
+      pos.r += PF_BK;
+      nsrc.kb += run_step;
+      nsrc.vb += run_step;
+      ncopy_kt = kt_target;
+    }
+  };
+
+  // A wave whose 32 query rows all lie beyond the chunk's end (the last query tile of a head) still sends its share
+  // of the copies and meets every barrier, but skips the fragments, MFMAs and softmax: its partner on the SIMD then
+  // has the issue slots to itself, and the matrix pipe does no work that is thrown away.
+  const bool has_rows = it.q0 + wave * (32 * NQB) < P.q_tokens;
+
+  if constexpr (NW == 8) {
   bf16x8 qf[1][NKS];
   attn_load_q<D, 1>(P, it, qf, tid);
 #pragma unroll
@@ -948,44 +1169,6 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     }
   };
 
-  // ---- plan of the next copy (made in one vector phase and carried out at the start of the next, so the
-  // scalar load of a frame's slot has a whole tile time to arrive) ----
-  TileSrc nsrc;
-  nsrc.kb = nsrc.vb = nsrc.kb2 = nsrc.vb2 = nullptr;
-  nsrc.simple = nsrc.split = false;
-  nsrc.n1 = 0;
-  int ncopy_kt = -1;                                           // tile planned for the next copy, -1: none
-  int run_left = 0;                                            // tiles after the planned one that continue its source run
-  long long run_step = 0;                                      // elements from one tile of the run to the next
-  auto plan_copy = [&](int kt_target) {
-    if (__builtin_expect(run_left <= 0, 0)) {
-      ncopy_kt = -1;
-      if (kt_target < it.kt1) {
-        tile_pos_advance(pos, H.n_sel, H.tpf);
-        nsrc = tile_src(kt_target, pos, H, D);
-        ncopy_kt = kt_target;
-        if (nsrc.simple) {
-          const int room = pos.j < H.n_sel ? H.tpf - pos.r : H.lkv - kt_target * PF_BK;   // keys from the tile's first row to the run's end
-          run_left = pf_min(room / PF_BK - 1, it.kt1 - 1 - kt_target);
-          run_step = (long long)PF_BK * (pos.j < H.n_sel ? D : H.cur_stride);
-        }
-      }
-    } else {
-      // common case: the tile follows a contiguous tile of the same frame (or of the chunk), is itself whole and
-      // inside it, and belongs to this work item: both sources move on by one tile, no slot lookup
-      --run_left;
-      pos.r += PF_BK;
-      nsrc.kb += run_step;
-      nsrc.vb += run_step;
-      ncopy_kt = kt_target;
-    }
-  };
-
-  // A wave whose 32 query rows all lie beyond the chunk's end (the last query tile of a head) still sends its share
-  // of the copies and meets every barrier, but skips the fragments, MFMAs and softmax: its partner on the SIMD then
-  // has the issue slots to itself, and the matrix pipe does no work that is thrown away.
-  const bool has_rows = it.q0 + wave * 32 < P.q_tokens;
-
   // ---- matrix phase: PV of the tile whose V sits in stage st_pv (its fragments 0 .. PP_RING-1 already
   // requested), QK of the tile whose K sits in stage st_qk ----
   auto m_phase = [&](auto has_pv, auto has_qk, int st_qk, int st_pv, int st_v_next) {
@@ -1022,21 +1205,7 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
     if (__builtin_expect(ncopy_kt >= 0, 1)) {
       const int snk = (sk_ + 3) & (PP_KSTAGES - 1);
       const int snv = sv_ >= 2 ? sv_ - 2 : sv_ + PP_VSTAGES - 2;
-      if (__builtin_expect(nsrc.simple && !nsrc.strided, 1)) {
-#pragma unroll
-        for (int h = 0; h < 4; ++h) copy_group(nsrc, snk, snv, h);
-        n_last = 4;
-      } else if (nsrc.simple) {
-#pragma unroll
-        for (int h = 0; h < 4; ++h) copy_group_strided(nsrc, snk, snv, h);
-        n_last = 4;
-      } else if (nsrc.split) {
-        n_last = copy_tile_split(nsrc, snk, snv);
-      } else {
-        pp_copy_rows_slow<false>(ncopy_kt, H, sK[snk], wave, lane);
-        pp_copy_rows_slow<true>(ncopy_kt, H, sV[snv], wave, lane);
-        n_last = 16;
-      }
+      n_last = copy_planned(nsrc, ncopy_kt, snk, snv);
     }
     plan_copy(kt + 4);
     if (__builtin_expect(!has_rows, 0)) {
@@ -1102,8 +1271,211 @@ __global__ __launch_bounds__(PP_WAVES * 64, 2) void pf_attn_pp_kernel(AttnParams
   m_phase(TagT(), TagF(), 0, sv, 0);
   if (grp == 0) __builtin_amdgcn_s_barrier();                  // group 0 waits for group 1's last phase
   __syncthreads();
+  } else {
+    // ================= 4 waves x 64 query rows, one wave per SIMD =================
+    // The wave's instruction stream is pipelined over half tiles of 32 keys.  Half step h issues, as ONE stream, the
+    // 16 MFMAs of O^T += V^T P^T for half tile h-1, the 16 MFMAs of S^T = K Q^T for half tile h+1, and between
+    // consecutive MFMAs a few instructions of the softmax of half tile h.  Every K / V^T fragment read from LDS feeds
+    // two MFMAs (the wave's two 32-row query blocks), which halves the LDS traffic per MFMA of the 8-wave form, and
+    // the matrix pipe of a SIMD is fed by one wave that never waits for a partner.  Scores and weights alternate
+    // between two register sets (A: first half of a tile, B: second half).  One workgroup barrier per tile, between
+    // its two half steps: the second one is the first to read the next tile's K.
+    bf16x8 qf[2][NKS];
+    attn_load_q<D, 2>(P, it, qf, tid);
+    static_for<0, 16>([&](auto n) {                             // Q^T goes to its accumulation registers
+      constexpr int N = decltype(n)::value;
+      w64_set_q<N>(__builtin_bit_cast(u32x4, qf[N / 8][N % 8]));
+    });
+    w64_zero_o();
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    int n_last = 0;                                            // copy instructions sent at the last barrier
+    __builtin_amdgcn_s_barrier();
+
+    f32x16 sA[2], sB[2];                                       // S^T of a half tile, per query block
+    bf16x8 pA[2][2], pB[2][2];                                 // P^T of a half tile: [query block][16-key chunk]
+    u32x2 vl[16], vh[16];
+    u32x4 kf[16];
+    float alpha[2] = {1.0f, 1.0f};
+    bool pending = false;                                      // the accumulators still have to be multiplied by alpha
+    // running state per query block: reference maximum m_run, m_run + lazy margin, m_run * scale, and the row sum in two
+    // halves (even and odd scores), all kept up to date where the reference maximum moves
+    float mthr[2] = {m_run[0] + thr, m_run[1] + thr}, mc[2] = {m_run[0] * c, m_run[1] * c};
+    float lsum[2][2] = {{0.0f, 0.0f}, {0.0f, 0.0f}};
+    float mx[2][2], ex[16][2];
+
+    auto rescale_pending = [&]() __attribute__((always_inline)) {
+      if (__builtin_expect(pending, 0)) w64_rescale(alpha[0], alpha[1]);
+      pending = false;
+    };
+    // softmax step K of the half tile whose scores are in s_cur; weights go to p_new
+    auto sm_step = [&](auto kk, auto &s_cur, auto &p_new) __attribute__((always_inline)) {
+      constexpr int K = decltype(kk)::value;
+      if constexpr (K < 16) {
+        constexpr int qb = K >> 3, ch = K & 1, j = (K & 7) >> 1, i = 8 * ch + 2 * j;   // block 0 first: block 1's last MFMA is the younger one
+        if constexpr (j == 0) asm("v_max_f32 %0, %1, %2" : "=v"(mx[qb][ch]) : "v"(s_cur[qb][i]), "v"(s_cur[qb][i + 1]));
+        else mx[qb][ch] = fmaxf(fmaxf(mx[qb][ch], s_cur[qb][i]), s_cur[qb][i + 1]);
+        if constexpr (j == 3) asm volatile("" : "+v"(mx[qb][ch]));   // results stay near their step: the optimizer would sink them to their uses
+      } else if constexpr (K == 16) {
+        const float m0 = fmaxf(mx[0][0], mx[0][1]), m1 = fmaxf(mx[1][0], mx[1][1]);
+        const unsigned long long over = __builtin_amdgcn_fcmpf(m0, mthr[0], 2 /* ogt */) | __builtin_amdgcn_fcmpf(m1, mthr[1], 2);
+        if (__builtin_expect(over != 0, 0)) {
+          const float mq[2] = {partner_max(m0), partner_max(m1)};
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb) {
+            const float m_new = fmaxf(m_run[qb], mq[qb]);
+            const float a = fast_exp2((m_run[qb] - m_new) * c);
+            alpha[qb] = pending ? alpha[qb] * a : a;
+            m_run[qb] = m_new;
+            mthr[qb] = m_new + thr;
+            mc[qb] = m_new * c;
+            lsum[qb][0] *= a;
+            lsum[qb][1] *= a;
+          }
+          pending = true;
+        }
+      } else {
+        constexpr int code = w64_bstep(K - W64_BSTEP0), kind = code / 16, u = code % 16;
+        constexpr int qb = u / 8, i = (u % 8) * 2;
+        if constexpr (kind == 0) {
+          ex[u][0] = fmaf(s_cur[qb][i], c, -mc[qb]);
+          ex[u][1] = fmaf(s_cur[qb][i + 1], c, -mc[qb]);
+          asm volatile("" : "+v"(ex[u][0]), "+v"(ex[u][1]));
+        } else if constexpr (kind == 1) {
+          ex[u][0] = fast_exp2(ex[u][0]);
+          ex[u][1] = fast_exp2(ex[u][1]);
+          asm volatile("" : "+v"(ex[u][0]), "+v"(ex[u][1]));
+        } else {
+          // row sum with plain fp32 adds: a dot-product instruction goes through the matrix pipe and queues there
+          lsum[qb][0] += ex[u][0];
+          lsum[qb][1] += ex[u][1];
+          p_new[qb][i >> 3][i & 7] = (__bf16)ex[u][0];
+          p_new[qb][i >> 3][(i & 7) + 1] = (__bf16)ex[u][1];
+          asm volatile("" : "+v"(lsum[qb][0]), "+v"(lsum[qb][1]), "+v"(p_new[qb][i >> 3]));
+        }
+      }
+    };
+    // One stream: PV part (V^T fragments IV0.. at lane address aVp, weights p_old), QK part (K fragments of key block
+    // KB at aK, scores to s_nxt), softmax of s_cur -> p_new spread over the MFMAs, prefetch of V^T fragments IVN.. at aVn.
+    auto stream = [&](auto pv, auto qk, auto sm, auto pre, auto iv0, auto kbq, auto ivn, auto &s_cur, auto &s_nxt, auto &p_old,
+                      auto &p_new, unsigned aK, unsigned aVp, unsigned aVn) __attribute__((always_inline)) {
+      constexpr bool PV = decltype(pv)::value, QK = decltype(qk)::value, SM = decltype(sm)::value, PRE = decltype(pre)::value;
+      constexpr int IV0 = decltype(iv0)::value, KB = decltype(kbq)::value, IVN = decltype(ivn)::value;
+      using S = W64Stream<PV, QK, PRE>;
+      constexpr int NC = S::NC, NSLOT = S::NSLOT;
+      auto issue = [&](auto pos) __attribute__((always_inline)) {
+        constexpr int PP = decltype(pos)::value;
+        if constexpr (PP < S::L) {
+          constexpr int kind = S::kind(PP), i = S::idx(PP);
+          if constexpr (kind == 0) pp_issue_frag<IV0 + i>(vl, vh, kf, 0u, aVp);
+          else if constexpr (kind == 1) pp_issue_frag<16 + i * 2 + KB>(vl, vh, kf, aK, 0u);
+          else pp_issue_frag<IVN + i>(vl, vh, kf, 0u, aVn);
+        }
+      };
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (!PV) static_for<0, PP_RING>([&](auto f) { issue(f); });   // with a PV part the previous half step has sent these
+      if constexpr (!PV && SM) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // no MFMA ahead of the first read of the scores
+      static_for<0, NSLOT>([&](auto sl) {
+        constexpr int SL = decltype(sl)::value, qb = SL % 2;
+        if constexpr (NC > 0) {
+          constexpr int p = SL / 2;
+          if constexpr (qb == 0) pp_wait_lgkm<S::wait_n(p)>();
+          constexpr int kind = S::kind(p), i = S::idx(p);
+          if constexpr (kind == 0) {
+            constexpr int I = IV0 + i;
+            const u32x4 a4 = __builtin_shufflevector(vl[I], vh[I], 0, 1, 2, 3);
+            w64_mfma_o<qb * 4 + I % 4>(a4, p_old[qb][i / 4]);
+          } else {
+            if constexpr (i == 0) w64_mfma_s0<qb * 8 + i>(s_nxt[qb], kf[i * 2 + KB]);
+            else w64_mfma_s<qb * 8 + i>(s_nxt[qb], kf[i * 2 + KB]);
+          }
+          if constexpr (qb == 1) issue(IntC<p + PP_RING>());
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (SM) {
+          static_for<w64_first_step(SL, NSLOT), w64_first_step(SL + 1, NSLOT)>([&](auto kk) { sm_step(kk, s_cur, p_new); });
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      });
+      // the PV part is long complete: the accumulators follow the moved maximum before the next half step adds to them
+      if constexpr (SM) rescale_pending();
+    };
+    // Between a tile's two half steps: this wave's rows of tile kt+1 have landed once only the copies of its last such
+    // point are outstanding; after the barrier that holds for every wave's rows, and every wave is done with K of tile
+    // kt-1 and V of tile kt-2.  The copies of tile kt+3 go into those stages, and the copy after that is planned.
+    int sk = 0, sv = 0;                                        // K and V stage of tile kt
+    auto tile_sync = [&](int kt) __attribute__((always_inline)) {
+      wait_copies(n_last);
+      __builtin_amdgcn_s_barrier();
+      n_last = 0;
+      if (__builtin_expect(ncopy_kt >= 0, 1)) {
+        const int snk = (sk + 3) & (PP_KSTAGES - 1);
+        const int snv = sv >= 2 ? sv - 2 : sv + PP_VSTAGES - 2;
+        n_last = copy_planned(nsrc, ncopy_kt, snk, snv);
+      }
+      plan_copy(kt + 4);
+    };
+    auto mask_tail = [&](auto &s_cur, int key0, int kt) __attribute__((always_inline)) {
+      const int valid = H.lkv - kt * BK - key0;                 // ragged tail: only the head's last tile
+      if (__builtin_expect(valid < 32, 0)) {
+        int g_l = g;
+        asm volatile("" : "+v"(g_l));                            // rare path: its per-lane constants are not held in registers
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (8 * (i >> 2) + 4 * g_l + (i & 3) >= valid) s_cur[0][i] = s_cur[1][i] = -INFINITY;
+      }
+    };
+    // Every tile runs the same two half steps, so that the loop has one body and every register set one place where
+    // it is written.  The ends of an item are absorbed by work whose result is not used: the first half step's PV part
+    // multiplies weights that are all zero (with V rows of the item's first tile), the last one's QK part computes
+    // scores of a tile that does not exist from whatever its K stage holds (16 MFMAs each, of ~64 per tile).
+    // first half step of tile kt: softmax of its keys 0..31 (set A); PV of tile kt-1's keys 32..63; QK of its keys 32..63
+    auto half0 = [&](int kt, bool first) __attribute__((always_inline)) {
+      if (__builtin_expect(has_rows, 1)) {
+        mask_tail(sA, 0, kt);
+        const unsigned aK = ak + (unsigned)(sk * PP_TILE_BYTES);
+        const unsigned aVn = av + (unsigned)(sv * PP_TILE_BYTES);
+        const unsigned aVp = first ? aVn : av + (unsigned)((sv == 0 ? PP_VSTAGES - 1 : sv - 1) * PP_TILE_BYTES);
+        stream(TagT(), TagT(), TagT(), TagT(), IntC<8>(), IntC<1>(), IntC<0>(), sA, sB, pB, pA, aK, aVp, aVn);
+      }
+    };
+    // second half step of tile kt: softmax of its keys 32..63 (set B); PV of its keys 0..31; QK of tile kt+1's keys 0..31
+    auto half1 = [&](int kt) __attribute__((always_inline)) {
+      if (__builtin_expect(has_rows, 1)) {
+        mask_tail(sB, 32, kt);
+        const unsigned aK = ak + (unsigned)(((sk + 1) & (PP_KSTAGES - 1)) * PP_TILE_BYTES);
+        const unsigned aV = av + (unsigned)(sv * PP_TILE_BYTES);
+        stream(TagT(), TagT(), TagT(), TagT(), IntC<0>(), IntC<0>(), IntC<8>(), sB, sA, pA, pB, aK, aV, aV);
+      }
+      sk = (sk + 1) & (PP_KSTAGES - 1);
+      sv = sv + 1 == PP_VSTAGES ? 0 : sv + 1;
+    };
+
+    plan_copy(it.kt0 + 3);
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pB[qb][ch][i] = (__bf16)0.0f;
+    if (__builtin_expect(has_rows, 1))                         // S^T of tile kt0's keys 0..31; V^T fragments for the first (empty) PV part
+      stream(TagF(), TagT(), TagF(), TagT(), IntC<0>(), IntC<0>(), IntC<8>(), sA, sA, pA, pA, ak, 0u, av);
+    for (int kt = it.kt0; kt < it.kt1; ++kt) {
+      half0(kt, kt == it.kt0);
+      tile_sync(kt);
+      half1(kt);
+    }
+    if (__builtin_expect(has_rows, 1)) {                       // PV of the last tile's keys 32..63 (its V stage is the one before sv now)
+      const unsigned aVp = av + (unsigned)((sv == 0 ? PP_VSTAGES - 1 : sv - 1) * PP_TILE_BYTES);
+      stream(TagT(), TagF(), TagF(), TagF(), IntC<8>(), IntC<0>(), IntC<0>(), sA, sA, pB, pB, 0u, aVp, 0u);
+    }
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");           // the last MFMA has written the accumulators back
+    static_for<0, 8>([&](auto n) { o[decltype(n)::value / 4][decltype(n)::value % 4] = w64_get_o<decltype(n)::value>(); });
+    l_run[0] = lsum[0][0] + lsum[0][1];
+    l_run[1] = lsum[1][0] + lsum[1][1];
+    __syncthreads();
+  }
   const AttnParams Pe = load_params();                         // read again: nothing of it is held through the loop above
-  attn_epilogue<D, 1, PP_WAVES>(Pe, it, o, m_run, l_run, (float *)&sK[0][0], &sFlag, tid);
+  attn_epilogue<D, NQB, NW>(Pe, it, o, m_run, l_run, (float *)&sK[0][0], &sFlag, tid);
   if (__builtin_expect(Pe.block_trace != nullptr, 0) && tid0 == 0) {
     const long long now = wall_clock64();
     sTrace[0] += now - sTrace[2];
@@ -1152,8 +1524,11 @@ extern "C" int pf_set_block_trace(void *dev_buffer, size_t bytes) {
 
 static int launch_attn(const AttnParams &P, int head_dim, int variant, int n_blocks, hipStream_t stream) {
   if (head_dim == 128 && variant == 1)
-    hipLaunchKernelGGL((pf_attn_pp_kernel<128>), dim3(P.tickets ? pf_min(n_blocks, pp_resident_workgroups()) : n_blocks),
-                       dim3(PP_WAVES * 64), 0, stream, P);
+    hipLaunchKernelGGL((pf_attn_pp_kernel<128, 8>), dim3(P.tickets ? pf_min(n_blocks, pp_resident_workgroups()) : n_blocks),
+                       dim3(8 * 64), 0, stream, P);
+  else if (head_dim == 128 && variant == 2)
+    hipLaunchKernelGGL((pf_attn_pp_kernel<128, 4>), dim3(P.tickets ? pf_min(n_blocks, pp_resident_workgroups()) : n_blocks),
+                       dim3(4 * 64), 0, stream, P);
   else if (head_dim == 128 && variant == 0)
     hipLaunchKernelGGL((pf_attn_kernel<128>), dim3(n_blocks), dim3(ATT_THREADS), 0, stream, P);
   else if (head_dim == 64 && variant == 0)

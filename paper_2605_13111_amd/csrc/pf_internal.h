@@ -16,10 +16,10 @@ constexpr int PF_DEFAULT_SEG_TILES = 128;
 constexpr int PF_MAX_SEL = 1024;        // slot table kept in LDS by the attention kernel
 constexpr int PF_MAX_HEADS = 1024;      // one index-kernel thread per head
 constexpr int PF_NUM_XCD = 8;           // MI355X: 8 accelerator dies, workgroup i runs on die i % 8
-constexpr int PF_NUM_VARIANTS = 2;
+constexpr int PF_NUM_VARIANTS = 3;
 constexpr int PF_DEFAULT_VARIANT = 1;   // for head_dim 128; other head sizes always use variant 0
 
-// query rows per workgroup of kernel variant v: 0 = 4 waves x 32 rows, 1 = 8 waves x 32 rows
+// query rows per workgroup of kernel variant v: 0 = 4 waves x 32 rows, 1 = 8 waves x 32 rows, 2 = 4 waves x 64 rows
 PF_HD int pf_variant_bq(int variant) { return variant == 0 ? 128 : 256; }
 
 PF_HD int pf_ceil_div(int a, int b) { return (a + b - 1) / b; }

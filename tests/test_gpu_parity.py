@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 DEFAULT_VARIANT = 1
 
 
-@pytest.fixture(params=[0, 1], ids=["w4x32", "pp8x32"])
+@pytest.fixture(params=[0, 1, 2], ids=["w4x32", "pp8x32", "w4x64"])
 def variant(request):
     B.pf_set_tuning(attn_variant=request.param)
     yield request.param
