@@ -194,7 +194,8 @@ int pf_plan_segments(const pf_pool *pool, int T, int q_tokens, int32_t *seg_tile
 
 /* Process-wide tuning switches, for tests and A/B measurements.  Each argument: -1 = leave unchanged.
  *   attn_variant  attention kernel for head_dim 128: 0 = 4 waves x 32 query rows, staged through registers;
- *                 1 = 8 waves x 32 rows in two alternating groups (the default)
+ *                 1 = 8 waves x 32 rows in two alternating groups (the default);
+ *                 2 = 4 waves x 64 rows, one wave per SIMD (measured slower than 1; kept selectable)
  *   attn_queue    1 = resident workgroups fed from per-die work queues (default), 0 = one work item per workgroup
  *   seg_tiles     key tiles per work item for every head, 0 = planned per launch (default)
  *   plan_uniform  1 = the planner stops after choosing one segment length for all heads
@@ -204,7 +205,7 @@ int pf_plan_segments(const pf_pool *pool, int T, int q_tokens, int32_t *seg_tile
 int pf_set_tuning(int attn_variant, int attn_queue, int seg_tiles, int plan_uniform);
 
 /* Diagnostics (process-wide, off by default): while a buffer is set, every work-queue launch of the pipelined
- * attention kernel (variant 1) makes each of its resident workgroups -- one per compute unit -- write four int64 words
+ * attention kernel (variants 1 and 2) makes each of its resident workgroups -- one per compute unit -- write four int64 words
  * at dev_buffer + 32 * workgroup: ticks of the device's constant 100 MHz clock spent inside work items, the
  * start of its first item, the end of its last item, and the number of items it ran.  A launch with more
  * resident workgroups than bytes / 32 writes nothing.  Each launch overwrites the last one's figures; NULL switches

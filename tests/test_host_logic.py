@@ -258,3 +258,29 @@ def test_launch_plan_rejects_bad_arguments():
     assert lib.pf_plan_segments(ctypes.byref(pool), 3, 0, None, None, None) == B.PF_ERR_INVALID_ARG
     assert lib.pf_plan_segments(ctypes.byref(pool), 9, 4680, None, None, None) == B.PF_ERR_INVALID_ARG   # 9 frames > 4 slots
     assert lib.pf_plan_segments(ctypes.byref(pool), 3, 4680, None, None, None) == B.PF_OK
+
+
+def test_tuning_accepts_every_kernel_variant():
+    for v in (0, 1, 2):
+        assert B.lib().pf_set_tuning(v, -1, -1, -1) == B.PF_OK
+    assert B.lib().pf_set_tuning(3, -1, -1, -1) == B.PF_ERR_INVALID_ARG
+    B.pf_set_tuning(attn_variant=1)
+
+
+def test_build_refuses_a_listing_where_the_compiler_uses_the_hidden_registers():
+    """The 64-row attention kernel owns accumulation registers a64..a255 through asm statements; the build reads the device
+    listing and must fail when an instruction outside those statements touches a register from a32 up."""
+    from paper_2605_13111_amd import build as BLD
+
+    def listing(body):
+        return "\n".join(["other_kernel:", "\tv_accvgpr_write_b32 a200, v0", "\ts_endpgm", BLD.W64_KERNEL + ":"] + body + ["\ts_endpgm"])
+
+    ok = ["\tv_accvgpr_write_b32 a3, v0", "\t;;#ASMSTART", "\tv_mfma_f32_32x32x16_bf16 a[64:79], v[0:3], v[4:7], a[64:79]",
+          "\t;;#ASMEND", "\tv_accvgpr_read_b32 v1, a3 ; a77 in a comment does not count"]
+    assert BLD.check_hidden_registers(listing(ok)) == 3
+    assert BLD.check_hidden_registers(listing(["\tv_add_f32 v0, v1, v2"])) == -1
+    for bad in ("\tv_accvgpr_write_b32 a64, v0", "\tscratch_load_dwordx4 a[40:43], off, off", "\tv_accvgpr_mov_b32 a32, a1"):
+        with pytest.raises(RuntimeError):
+            BLD.check_hidden_registers(listing(ok + [bad]))
+    with pytest.raises(RuntimeError):
+        BLD.check_hidden_registers("other_kernel:\n\ts_endpgm")
