@@ -48,6 +48,10 @@ def parse():
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="also run one plain device-to-device copy of this many MiB (a dispatch of known size "
                          "against which hardware traffic counters are scaled)")
+    ap.add_argument("--append-probe", action="store_true",
+                    help="instead of the benchmark: a few pool appends of known size (12 heads that keep every frame, then "
+                         "12 top-6 heads whose survivors move) and a 64 MiB device copy, each announced with its "
+                         "algorithmic bytes; for reading hardware traffic counters of the append kernel")
     return ap.parse_args()
 
 
@@ -62,6 +66,8 @@ def main():
     B.lib()                                           # fail loudly if libpf.so is missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.append_probe:
+        return append_probe(B, synth, dev)
     if args.workload in ("c5_stream", "c6_paper", "c7_headwin"):
         return stream_bench(args, B, synth, dev)
     w = synth.WORKLOADS[args.workload]
@@ -184,6 +190,7 @@ def main():
     achieved = flops_per_launch / (attn_ms_avg * 1e-3) / 1e12
     value = flops / (ms_per_step * 1e-3) / 1e12
 
+    traffic, traffic_source = profiled_traffic(w.name, int(layers[0][1].c.variant), args.layout)
     result = {
         "metric": "ragged-attn effective TFLOP/s (retained keys)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -196,9 +203,9 @@ def main():
                    "attn_variant": int(layers[0][1].c.variant), "chunk_layout": args.layout,
                    "seg_tiles": int(os.environ.get("PF_SEG_TILES", "0")) or "default"},
         "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
-        "roofline": {"kernel": "pf_attn_pp_kernel" if int(layers[0][1].c.variant) == 1 else "pf_attn_kernel", "bound": "mfma", "achieved": round(achieved, 2),
+        "roofline": {"kernel": "pf_attn_pp_kernel" if int(layers[0][1].c.variant) >= 1 else "pf_attn_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": profiled_traffic(w.name, int(layers[0][1].c.variant), args.layout),
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "avg_launch_ms": round(attn_ms_avg, 4),
                      "flop_per_launch": flops_per_launch, "launches_timed": len(attn_ms)},
         "pool_append": {"kernel": "pf_pool_append_kernel", "bound": "hbm",
@@ -260,19 +267,61 @@ def main():
 
 
 def profiled_traffic(workload, variant, layout):
-    """HBM bytes per attention launch from the committed rocprofv3 counter summary of this command (FETCH_SIZE and
-    WRITE_SIZE passes, scaled by the copy probe); counters cannot be read inside a timed run.  None when the
-    summary does not cover this workload / kernel."""
+    """(HBM bytes per attention launch, where the figure comes from): counters cannot be read inside a timed run, so
+    the bytes are those of the committed rocprofv3 counter summary of this command (FETCH_SIZE and WRITE_SIZE passes,
+    scaled by the copy probe).  The summary names the commit it was made from and the SHA-256 of the attention
+    kernel's source at that time; when the source here differs, or the summary does not cover this workload /
+    kernel, the bytes are None and the second value says why."""
+    rel = "profiles/pf_attn_pp_kernel_c3_step.md"
     if workload != "c3_step" or variant != 1 or layout != "packed":
-        return None
-    path = os.path.join(ROOT, "profiles", "pf_attn_pp_kernel_c3_step.md")
+        return None, "no stored counter summary for this workload / kernel / layout"
+    import hashlib
+    fields = {}
     try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return int(line.split(":")[1])
+        for line in open(os.path.join(ROOT, rel)):
+            for key in ("traffic_bytes_per_launch", "commit", "kernel_source_sha256"):
+                if line.startswith(key + ":"):
+                    fields[key] = line.split(":", 1)[1].strip()
+        with open(os.path.join(ROOT, "paper_2605_13111_amd", "csrc", "pf_attn.hip"), "rb") as f:
+            sha = hashlib.sha256(f.read()).hexdigest()
     except OSError:
-        pass
-    return None
+        return None, "no stored counter summary"
+    if "traffic_bytes_per_launch" not in fields:
+        return None, "no stored counter summary"
+    where = "%s @ %s" % (rel, fields.get("commit", "unknown commit"))
+    if fields.get("kernel_source_sha256") != sha:
+        return None, "stale: %s was measured on another version of the attention kernel" % where
+    return int(fields["traffic_bytes_per_launch"]), "stored rocprofv3 counters, " + where
+
+
+def append_probe(B, synth, dev):
+    """Pool appends whose algorithmic bytes are known exactly, beside a plain copy (see --append-probe)."""
+    H, D, tpf = 12, 128, 1560
+    frame = tpf * D * 2
+
+    def run(pols, n_app, label):
+        pool = B.Pool(pols, tpf, D, device=dev)
+        B.pf_pool_reset(pool)
+        k = synth.randn_bf16((H, 3, tpf, D), 1, device=dev)
+        v = synth.randn_bf16((H, 3, tpf, D), 2, device=dev)
+        sc = synth.frame_scores(H, 3, 3, device=dev)
+        torch.cuda.synchronize()
+        for i in range(n_app):
+            before = pool.frame_ids.cpu().numpy().copy()
+            B.pf_cache_append(pool, k, v, sc)
+            torch.cuda.synchronize()
+            after = pool.frame_ids.cpu().numpy()
+            moved = int(((after != before) & (after >= 0) & (after < 3 * i)).sum())
+            print("%s append %d: %d new frames, %d survivors moved -> algorithmic read = write = %.2f MB (K and V)"
+                  % (label, i, H * 3, moved, 2 * frame * (H * 3 + moved) / 1e6), flush=True)
+
+    run([synth.anchor_all(30)] * H, 4, "keep-all")
+    run([synth.anchor_topk(6, 6)] * H, 6, "top-6")
+    src = torch.empty(64 << 20, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    print("copy probe: 64 MiB read, 64 MiB written", flush=True)
 
 
 def stream_bench(args, B, synth, dev):
@@ -356,6 +405,7 @@ def stream_bench(args, B, synth, dev):
         "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "roofline": {"kernel": "pf_attn_pp_kernel", "bound": "mfma", "achieved": round(value, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(value / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "traffic_source": "no stored counter summary for this workload",
                      "note": "whole-rollout rate (appends and index builds included in the time)"}}))
 
 
