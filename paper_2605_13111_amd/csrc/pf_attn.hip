@@ -1169,6 +1169,19 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void pf_attn_pp_kernel(At
     }
   };
 
+  float mthr = m_run[0] + thr, mc = m_run[0] * c, l_odd = 0.0f;   // reference maximum + lazy margin, * scale; odd scores' row sum
+  // weights of two scores (key block kb, registers i and i+1): scale, exp2, add to the row sums (even scores into l_run,
+  // odd ones into l_odd; plain fp32 adds: a dot-product instruction goes through the matrix pipe and queues there behind
+  // the other group's MFMAs, measured ~54 cycles each next to a saturated MFMA stream, against 4 alone), round to bf16
+  auto softmax_pair = [&](auto kbv, auto iv) __attribute__((always_inline)) {
+    constexpr int kb = decltype(kbv)::value, i = decltype(iv)::value;
+    const float e0 = fast_exp2(fmaf(s[kb][i], c, -mc));
+    const float e1 = fast_exp2(fmaf(s[kb][i + 1], c, -mc));
+    l_run[0] += e0;
+    l_odd += e1;
+    pf[kb * 2 + (i >> 3)][i & 7] = (__bf16)e0;
+    pf[kb * 2 + (i >> 3)][(i & 7) + 1] = (__bf16)e1;
+  };
   // ---- matrix phase: PV of the tile whose V sits in stage st_pv (its fragments 0 .. PP_RING-1 already
   // requested), QK of the tile whose K sits in stage st_qk ----
   auto m_phase = [&](auto has_pv, auto has_qk, int st_qk, int st_pv, int st_v_next) {
@@ -1222,38 +1235,31 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void pf_attn_pp_kernel(At
         for (int i = 0; i < 16; ++i)
           if (kb * 32 + 8 * (i >> 2) + 4 * g_l + (i & 3) >= valid) s[kb][i] = -INFINITY;
     }
-    float mx = s[0][0];
+    // maximum of this lane's 32 scores (two chains, one per key block); the check against the reference maximum is
+    // local: the two lanes of a query column exchange their maxima only when one of them has to move it
+    float mx0, mx1;
+    asm("v_max_f32 %0, %1, %2" : "=v"(mx0) : "v"(s[0][0]), "v"(s[0][1]));   // asm: no canonicalising of the MFMA's results
+    asm("v_max_f32 %0, %1, %2" : "=v"(mx1) : "v"(s[1][0]), "v"(s[1][1]));
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
-    mx = partner_max(mx);
-    if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx > m_run[0] + thr) != 0, 0)) {
-      const float m_new = fmaxf(m_run[0], mx);
+    for (int i = 2; i < 16; i += 2) {
+      mx0 = fmaxf(fmaxf(mx0, s[0][i]), s[0][i + 1]);
+      mx1 = fmaxf(fmaxf(mx1, s[1][i]), s[1][i + 1]);
+    }
+    const float mxl = fmaxf(mx0, mx1);
+    if (__builtin_expect(__builtin_amdgcn_fcmpf(mxl, mthr, 2 /* ogt */) != 0, 0)) {
+      const float m_new = fmaxf(m_run[0], partner_max(mxl));
       const float alpha = fast_exp2((m_run[0] - m_new) * c);
       m_run[0] = m_new;
+      mthr = m_new + thr;
+      mc = m_new * c;
       l_run[0] *= alpha;
+      l_odd *= alpha;
 #pragma unroll
       for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[0][db][i] *= alpha;
     }
-    const float mc = m_run[0] * c;
-    // row sum with plain fp32 adds: a dot-product instruction goes through the matrix pipe and queues there
-    // behind the other group's MFMAs (measured: ~54 cycles each next to a saturated MFMA stream, against 4 alone)
-    float ls0 = 0.f, ls1 = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; i += 2) {
-        const float e0 = fast_exp2(fmaf(s[kb][i], c, -mc));
-        const float e1 = fast_exp2(fmaf(s[kb][i + 1], c, -mc));
-        ls0 += e0;
-        ls1 += e1;
-        pf[kb * 2 + (i >> 3)][i & 7] = (__bf16)e0;
-        pf[kb * 2 + (i >> 3)][(i & 7) + 1] = (__bf16)e1;
-      }
-    l_run[0] += ls0 + ls1;
+    static_for<0, 16>([&](auto j) { softmax_pair(IntC<decltype(j)::value / 8>(), IntC<2 * (decltype(j)::value % 8)>()); });
     __builtin_amdgcn_s_barrier();
   };
 
@@ -1270,6 +1276,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void pf_attn_pp_kernel(At
   }
   m_phase(TagT(), TagF(), 0, sv, 0);
   if (grp == 0) __builtin_amdgcn_s_barrier();                  // group 0 waits for group 1's last phase
+  l_run[0] += l_odd;
   __syncthreads();
   } else {
     // ================= 4 waves x 64 query rows, one wave per SIMD =================
