@@ -94,3 +94,18 @@ def test_paper_default_rollouts_to_240_frames(name):
     pols = synth.policies(name, layer=1, slots_of=helpers.oracle_slots(w.history_frames))
     check_at = set(range(24, 241, 24)) | {3, 9}
     _rollout(pols, w.tokens_per_frame, w.head_dim, 3, 80, 700 + len(name), check_at, {120, 237}, 32, name)
+
+
+def test_c3_step_layers_with_the_64_row_kernel():
+    """Two layers of the 30-layer step (their own per-head segment plans) through kernel variant 2 (4 waves x 64 query
+    rows): pool and index in full, attention on 16 sampled rows per head."""
+    w = synth.WORKLOADS["c3_step"]
+    B.pf_set_tuning(attn_variant=2)
+    try:
+        for layer in (5, 22):
+            pols = synth.policies("c3_step", layer=layer)
+            T = w.history_frames
+            _rollout(pols, w.tokens_per_frame, w.head_dim, 3, T // 3 + 1, 800 + layer, {T}, {T}, 16,
+                     "c3_step layer %d, 64-row kernel" % layer, append_last=False)
+    finally:
+        B.pf_set_tuning(attn_variant=1)
