@@ -25,6 +25,7 @@ import torch
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
+APPEND_STREAMS = 4                    # side streams that take the layers' write-backs (appends, index builds) in a rollout
 
 
 def parse():
@@ -112,14 +113,25 @@ def main():
             q, k_cur, v_cur = [t.permute(1, 0, 2).contiguous().permute(1, 0, 2) for t in (q, k_cur, v_cur)]
         out = torch.empty_like(q)                  # preserves the strides
         layers.append((pool, index, q, k_cur, v_cur, out))
-    # The last append of every layer (the one that brings its pool to T frames), enqueued back to back as in a
-    # rollout and timed as one region; bytes = new frames + survivors that changed slot, K and V, read + write.
+    # The last append of every layer (the one that brings its pool to T frames), enqueued as in a rollout, where the
+    # layers' write-backs are independent of each other and go round-robin onto four side streams (default priority),
+    # and timed as one region on the main stream; bytes = new frames + survivors that changed slot, K and V, read + write.
     torch.cuda.synchronize()
     ids_before = [a[0].frame_ids.cpu().numpy().copy() for a in last_appends]
+    wb_streams = [torch.cuda.Stream() for _ in range(APPEND_STREAMS)]
+    for s_ in wb_streams:                            # first use of a stream costs the host a few hundred microseconds
+        with torch.cuda.stream(s_):
+            torch.zeros(1024, device=dev).add_(1)
+    torch.cuda.synchronize()
+    main0 = torch.cuda.current_stream()
     e0, e1 = ev(), ev()
     e0.record()
-    for pool, k_new, v_new, sc, t0, n_new in last_appends:
-        B.pf_cache_append(pool, k_new, v_new, sc)
+    for s_ in wb_streams:
+        s_.wait_stream(main0)
+    for li, (pool, k_new, v_new, sc, t0, n_new) in enumerate(last_appends):
+        B.pf_cache_append(pool, k_new, v_new, sc, stream=wb_streams[li % APPEND_STREAMS].cuda_stream)
+    for s_ in wb_streams:
+        main0.wait_stream(s_)
     e1.record()
     torch.cuda.synchronize()
     append_ms.append(e0.elapsed_time(e1) / len(last_appends))
@@ -210,7 +222,8 @@ def main():
                      "flop_per_launch": flops_per_launch, "launches_timed": len(attn_ms)},
         "pool_append": {"kernel": "pf_pool_append_kernel", "bound": "hbm",
                         "what": "the append of %d frames that brings each layer's pool to %d frames "
-                                "(new frames + left-packed survivors, K and V, read + write), all layers enqueued back to back" % (w.chunk_frames, T),
+                                "(new frames + left-packed survivors, K and V, read + write), the layers' appends enqueued "
+                                "round-robin on %d streams as in a rollout, timed as one region" % (w.chunk_frames, T, APPEND_STREAMS),
                         "avg_launch_ms": round(float(np.mean(append_ms)), 4),
                         "achieved": round(float(np.sum(append_bytes)) / (float(np.sum(append_ms)) * 1e-3) / 1e9, 1),
                         "peak": PEAK_HBM_GBS, "unit": "GB/s",
