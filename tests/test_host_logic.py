@@ -284,3 +284,17 @@ def test_build_refuses_a_listing_where_the_compiler_uses_the_hidden_registers():
             BLD.check_hidden_registers(listing(ok + [bad]))
     with pytest.raises(RuntimeError):
         BLD.check_hidden_registers("other_kernel:\n\ts_endpgm")
+
+
+def test_stored_counter_summary_belongs_to_this_attention_kernel():
+    """bench.py takes roofline.traffic from profiles/pf_attn_pp_kernel_c3_step.md only when that summary was made from
+    this very pf_attn.hip (SHA-256 recorded in the summary); a summary of another version makes the field null."""
+    sys_path_root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("pf_bench", os.path.join(sys_path_root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    traffic, source = bench.profiled_traffic("c3_step", 1, "packed")
+    assert traffic is not None and traffic > 100e6 and "profiles/pf_attn_pp_kernel_c3_step.md @" in source, source
+    assert bench.profiled_traffic("c3_step", 2, "packed")[0] is None
+    assert bench.profiled_traffic("c5_stream", 1, "packed")[0] is None
