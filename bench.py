@@ -232,15 +232,16 @@ def main():
 
     if args.block_trace:
         # one resident workgroup per compute unit: ticks (10 ns) inside work items over the launch's span
-        trace = torch.zeros(4 * 1024, dtype=torch.int64, device=dev)
+        trace = torch.zeros(8 * 1024, dtype=torch.int64, device=dev)
         B.pf_set_block_trace(trace)
-        fracs, spans = [], []
+        fracs, spans, mhz = [], [], []
         for (pool, index, q, k_cur, v_cur, out) in layers:
             trace.zero_()
             attn_fwd(pool, index, q, k_cur, v_cur, out, workspace)
             torch.cuda.synchronize()
-            t = trace.cpu().numpy().reshape(-1, 4)
+            t = trace.cpu().numpy().reshape(-1, 8)
             t = t[t[:, 3] > 0]
+            mhz.append(100.0 * t[:, 4] / np.maximum(t[:, 0], 1))
             span = float(t[:, 2].max() - t[:, 1].min())
             fracs.append(t[:, 0] / span)
             spans.append(span * 1e-2)
@@ -250,7 +251,11 @@ def main():
                                      "resident workgroup (one per compute unit) spent inside work items, over %d launch(es)" % len(layers),
                              "workgroups_per_launch": int(len(fracs[0])), "mean": round(float(allf.mean()), 4),
                              "min": round(float(allf.min()), 4), "p05": round(float(np.percentile(allf, 5)), 4),
-                             "max": round(float(allf.max()), 4), "mean_span_us": round(float(np.mean(spans)), 1)}
+                             "max": round(float(allf.max()), 4), "mean_span_us": round(float(np.mean(spans)), 1),
+                             "shader_clock_mhz": {"what": "shader-clock cycles per 100 MHz tick inside work items, per workgroup",
+                                                  "mean": round(float(np.concatenate(mhz).mean()), 0),
+                                                  "min": round(float(np.concatenate(mhz).min()), 0),
+                                                  "max": round(float(np.concatenate(mhz).max()), 0)}}
 
     # ---------------------------------------------------------------- cpu_baseline: the oracle on a bounded sample
     if not args.no_cpu:

@@ -205,11 +205,12 @@ int pf_plan_segments(const pf_pool *pool, int T, int q_tokens, int32_t *seg_tile
 int pf_set_tuning(int attn_variant, int attn_queue, int seg_tiles, int plan_uniform);
 
 /* Diagnostics (process-wide, off by default): while a buffer is set, every work-queue launch of the pipelined
- * attention kernel (variants 1 and 2) makes each of its resident workgroups -- one per compute unit -- write four int64 words
- * at dev_buffer + 32 * workgroup: ticks of the device's constant 100 MHz clock spent inside work items, the
- * start of its first item, the end of its last item, and the number of items it ran.  A launch with more
- * resident workgroups than bytes / 32 writes nothing.  Each launch overwrites the last one's figures; NULL switches
- * it off.  The buffer must stay valid while launches that were enqueued with it may run. */
+ * attention kernel (variants 1 and 2) makes each of its resident workgroups -- one per compute unit -- write int64 words
+ * at dev_buffer + 64 * workgroup: [0] ticks of the device's constant 100 MHz clock spent inside work items, [1] the
+ * start of its first item and [2] the end of its last item on that clock, [3] the number of items it ran, [4] shader-clock
+ * cycles spent inside work items ([4] / [0] x 100 MHz = the clock the compute unit really ran at); [5..7] unused.
+ * A launch with more resident workgroups than bytes / 64 writes nothing.  Each launch overwrites the last one's
+ * figures; NULL switches it off.  The buffer must stay valid while launches that were enqueued with it may run. */
 int pf_set_block_trace(void *dev_buffer, size_t bytes);
 
 /* ---- the hot path -------------------------------------------------------- */

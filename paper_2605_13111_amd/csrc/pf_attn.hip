@@ -56,7 +56,7 @@ struct AttnParams {
   // chunk tensors (q, k_cur, v_cur, out): element strides between tokens of a head and between heads
   // (packed [heads][tokens][D]: D and q_tokens*D; the model's [tokens][heads][D]: heads*D and D)
   long long tok_stride, head_stride;
-  // optional diagnostics (pf_set_block_trace): per resident workgroup {busy, first start, last end, items}, in ticks of the
+  // optional diagnostics (pf_set_block_trace): per resident workgroup {busy, first start, last end, items, busy shader cycles}, in ticks of the
   // constant 100 MHz clock; null = off
   long long *block_trace;
 };
@@ -874,7 +874,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void pf_attn_pp_kernel(At
   __shared__ __attribute__((aligned(1024))) char smem[(PP_KSTAGES + PP_VSTAGES) * PP_TILE_BYTES];
   __shared__ int32_t sFlag;
   __shared__ int32_t sNext;
-  __shared__ long long sTrace[4];                              // busy ticks, first start, this item's start, items (thread 0 only)
+  __shared__ long long sTrace[6];                              // busy ticks, first start, this item's start, items, busy shader-clock cycles, this item's start in those (thread 0 only)
   char (*sK)[PP_TILE_BYTES] = (char (*)[PP_TILE_BYTES])smem;
   char (*sV)[PP_TILE_BYTES] = sK + PP_KSTAGES;
   const int tid0 = threadIdx.x;
@@ -906,7 +906,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void pf_attn_pp_kernel(At
     R.tickets = as_global(R.tickets), R.workspace = as_global(R.workspace);
     return R;
   };
-  if (tid0 == 0) sTrace[0] = sTrace[1] = sTrace[2] = sTrace[3] = 0;
+  if (tid0 == 0) sTrace[0] = sTrace[1] = sTrace[2] = sTrace[3] = sTrace[4] = sTrace[5] = 0;
   int hop_v = 0;                               // dies given up so far; kept in a vector register between items
   while (true) {
   asm volatile("" : "+v"(hop_v));
@@ -939,6 +939,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void pf_attn_pp_kernel(At
     const long long now = wall_clock64();
     if (sTrace[3] == 0) sTrace[1] = now;
     sTrace[2] = now;
+    sTrace[5] = clock64();
   }
   int tid = tid0;
   asm volatile("" : "+v"(tid));               // per-lane constants are worked out anew for each item, not kept across the loop
@@ -1488,13 +1489,14 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void pf_attn_pp_kernel(At
     sTrace[0] += now - sTrace[2];
     sTrace[2] = now;                                           // doubles as "last end"
     sTrace[3] += 1;
+    sTrace[4] += clock64() - sTrace[5];
   }
   }
   {
     long long *bt = load_params().block_trace;
     if (__builtin_expect(bt != nullptr, 0) && tid0 == 0) {
-      bt = as_global(bt) + (size_t)blockIdx.x * 4;
-      bt[0] = sTrace[0]; bt[1] = sTrace[1]; bt[2] = sTrace[2]; bt[3] = sTrace[3];
+      bt = as_global(bt) + (size_t)blockIdx.x * 8;
+      bt[0] = sTrace[0]; bt[1] = sTrace[1]; bt[2] = sTrace[2]; bt[3] = sTrace[3]; bt[4] = sTrace[4];
     }
   }
   int32_t *tickets = load_params().tickets;
@@ -1523,7 +1525,7 @@ static int pp_resident_workgroups() {
 static long long *g_block_trace = nullptr;
 static size_t g_block_trace_bytes = 0;
 extern "C" int pf_set_block_trace(void *dev_buffer, size_t bytes) {
-  if (dev_buffer && ((((uintptr_t)dev_buffer) & 7u) || bytes < 32)) return PF_ERR_INVALID_ARG;
+  if (dev_buffer && ((((uintptr_t)dev_buffer) & 7u) || bytes < 64)) return PF_ERR_INVALID_ARG;
   g_block_trace = (long long *)dev_buffer;
   g_block_trace_bytes = dev_buffer ? bytes : 0;
   return PF_OK;
@@ -1594,7 +1596,7 @@ static int attn_fwd_impl(const pf_pool *pool, const pf_index *index, const void 
   P.tpf = pool->tokens_per_frame;
   P.q_tokens = q_tokens;
   P.n_qt = n_qt;
-  P.block_trace = (queue && g_block_trace_bytes >= (size_t)pf_min(index->n_blocks, pp_resident_workgroups()) * 32) ? g_block_trace : nullptr;
+  P.block_trace = (queue && g_block_trace_bytes >= (size_t)pf_min(index->n_blocks, pp_resident_workgroups()) * 64) ? g_block_trace : nullptr;
   P.tok_stride = layout ? layout->token_stride : pool->head_dim;
   P.head_stride = layout ? layout->head_stride : (long long)q_tokens * pool->head_dim;
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)pool->head_dim);
