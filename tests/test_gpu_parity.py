@@ -457,3 +457,42 @@ def test_head_classification_matches_the_oracle():
     oh, ot, op = OC.classify_heads(lg.numpy())
     assert np.array_equal(ptype.cpu().numpy(), ot) and np.array_equal(pper.cpu().numpy(), op)
     assert ot[0].tolist()[:8] == [0, 2, 0, 2, 1, 1, 0, 2]
+
+
+def test_pool_that_disagrees_with_the_host_plan_is_reported_and_attention_writes_nothing():
+    """A pool whose device tables do not hold what the policy asks for (here: the residency count of one head lowered, as if the
+    pool had not been filled through pf_cache_append): pf_build_index sets the index's device status word and leaves an
+    empty plan, the attention launch on it writes nothing; after the table is restored the same index works again."""
+    dev = "cuda:0"
+    pols = [synth.anchor_all(12), synth.wave(2, 12), synth.anchor_topk(3, 3), synth.veil(1, 3)]
+    tpf, D, Lq, H = 48, 128, 96, 4
+    pool = B.Pool(pols, tpf, D, device=dev)
+    B.pf_pool_reset(pool)
+    for c in range(3):
+        B.pf_cache_append(pool, synth.randn_bf16((H, 3, tpf, D), 40 + c, device=dev), synth.randn_bf16((H, 3, tpf, D), 50 + c, device=dev),
+                          synth.frame_scores(H, 3, 60 + c, device=dev))
+    index = B.Index(pool, Lq)
+    q, k_cur, v_cur = [synth.randn_bf16((H, Lq, D), 70 + i, device=dev) for i in range(3)]
+    ws = torch.empty(max(B.pf_attn_workspace_bytes(pool, Lq), 16), dtype=torch.uint8, device=dev)
+    B.pf_build_index(pool, index, Lq)
+    assert B.pf_index_status(index) == 0
+    good = torch.full((H, Lq, D), float("nan"), dtype=torch.bfloat16, device=dev)
+    B.pf_ragged_attn_fwd(pool, index, q, k_cur, v_cur, good, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(good.float()).all()
+
+    saved = pool.n_frames[:1].clone()
+    pool.n_frames[:1] = saved - 1                            # head 0 (keeps everything) now counts one frame fewer
+    B.pf_build_index(pool, index, Lq)
+    assert B.pf_index_status(index) != 0
+    out = torch.full((H, Lq, D), float("nan"), dtype=torch.bfloat16, device=dev)
+    B.pf_ragged_attn_fwd(pool, index, q, k_cur, v_cur, out, ws)
+    torch.cuda.synchronize()
+    assert torch.isnan(out.float()).all(), "attention wrote output from an invalid plan"
+
+    pool.n_frames[:1] = saved
+    B.pf_build_index(pool, index, Lq)
+    assert B.pf_index_status(index) == 0
+    B.pf_ragged_attn_fwd(pool, index, q, k_cur, v_cur, out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), good.view(torch.int16))
